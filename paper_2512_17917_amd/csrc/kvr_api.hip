@@ -1,0 +1,223 @@
+// C ABI of libkvr: argument validation, workspace planning, dispatch.
+// Everything that can be checked on the host is checked before the first HIP
+// call, so the error paths work on a machine without a GPU.
+#include <string.h>
+
+#include "kvr_launch.h"
+
+namespace {
+
+thread_local int32_t g_last_hip_error = 0;
+
+constexpr uint64_t LCG_MUL = 6364136223846793005ull;
+constexpr uint64_t LCG_INC = 1442695040888963407ull;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Returns KVR_OK and fills `d`, or an error code.
+int32_t check_desc(const kvr_desc* desc, kvr::DevDesc& d) {
+  if (desc == nullptr) return KVR_ERR_INVALID_ARG;
+  if (desc->batch < 1 || desc->n_q_heads < 1 || desc->n_kv_heads < 1) return KVR_ERR_INVALID_ARG;
+  if (desc->r < 1 || desc->r > KVR_MAX_ROWS || desc->w < 1 || desc->w > 65536) return KVR_ERR_INVALID_ARG;
+  if (desc->dtype != KVR_F32 && desc->dtype != KVR_BF16) return KVR_ERR_INVALID_ARG;
+  if (desc->sign_mask < 0 || desc->sign_mask > 3) return KVR_ERR_INVALID_ARG;
+  if (desc->median_mode != KVR_MEDIAN_MIDMEAN && desc->median_mode != KVR_MEDIAN_LOWER)
+    return KVR_ERR_INVALID_ARG;
+  if (!(desc->softmax_scale == desc->softmax_scale)) return KVR_ERR_INVALID_ARG;
+  if (desc->head_dim != KVR_HEAD_DIM) return KVR_ERR_UNSUPPORTED;
+  if (desc->n_q_heads % desc->n_kv_heads != 0) return KVR_ERR_UNSUPPORTED;
+  const int G = desc->n_q_heads / desc->n_kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return KVR_ERR_UNSUPPORTED;
+  if ((long long)desc->batch * desc->n_kv_heads > 65535) return KVR_ERR_UNSUPPORTED;
+  d.B = desc->batch;
+  d.Hq = desc->n_q_heads;
+  d.Hkv = desc->n_kv_heads;
+  d.G = G;
+  d.r = desc->r;
+  d.w = desc->w;
+  d.sign_mask = desc->sign_mask;
+  d.median_mode = desc->median_mode;
+  d.scale = desc->softmax_scale;
+  memcpy(d.hp, desc->hash_params, sizeof(d.hp));
+  return KVR_OK;
+}
+
+int32_t finish(hipError_t e) {
+  if (e == hipSuccess) return KVR_OK;
+  g_last_hip_error = (int32_t)e;
+  return KVR_ERR_HIP;
+}
+
+constexpr long long MAX_TOKENS = 1ll << 30;
+
+}  // namespace
+
+extern "C" {
+
+const char* kvr_version(void) { return "kvr 0.1 (gfx950)"; }
+
+int32_t kvr_last_hip_error(void) { return g_last_hip_error; }
+
+int32_t kvr_hash_params_from_seed(uint64_t seed, int32_t r, uint64_t* out) {
+  if (out == nullptr || r < 1 || r > KVR_MAX_ROWS) return KVR_ERR_INVALID_ARG;
+  uint64_t x = seed;
+  for (int i = 0; i < r; ++i) {
+    for (int k = 0; k < 4; ++k) {
+      x = x * LCG_MUL + LCG_INC;
+      out[i * 4 + k] = x;
+    }
+    out[i * 4 + 0] |= 1ull;
+    out[i * 4 + 2] |= 1ull;
+  }
+  return KVR_OK;
+}
+
+int32_t kvr_hash_host(const kvr_desc* desc, int32_t J, int32_t* bucket, int32_t* sign) {
+  if (desc == nullptr || bucket == nullptr || sign == nullptr || J < 0) return KVR_ERR_INVALID_ARG;
+  if (desc->r < 1 || desc->r > KVR_MAX_ROWS || desc->w < 1 || desc->w > 65536) return KVR_ERR_INVALID_ARG;
+  for (int i = 0; i < desc->r; ++i) {
+    const uint64_t u = desc->hash_params[i][0] * (uint64_t)(uint32_t)J + desc->hash_params[i][1];
+    bucket[i] = (int32_t)(((u >> 32) * (uint64_t)(uint32_t)desc->w) >> 32);
+    const uint64_t s = desc->hash_params[i][2] * (uint64_t)(uint32_t)J + desc->hash_params[i][3];
+    sign[i] = (s >> 63) ? -1 : 1;
+  }
+  return KVR_OK;
+}
+
+int32_t kvr_workspace_size(const kvr_desc* desc, int32_t op, int64_t n_max, size_t* bytes) {
+  kvr::DevDesc d;
+  const int32_t rc = check_desc(desc, d);
+  if (rc != KVR_OK) return rc;
+  if (bytes == nullptr || n_max < 0 || n_max > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  switch (op) {
+    case KVR_OP_SELECT:
+    case KVR_OP_RECONSTRUCT:
+      *bytes = 0;
+      return KVR_OK;
+    case KVR_OP_ENCODE:
+      *bytes = kvr::encode_plan(d, n_max).total_bytes;
+      return KVR_OK;
+    case KVR_OP_ATTEND:
+      *bytes = kvr::attend_plan(d, n_max).total_bytes;
+      return KVR_OK;
+    default:
+      return KVR_ERR_INVALID_ARG;
+  }
+}
+
+int32_t kvr_append(const kvr_desc* desc, const void* k_new, const void* v_new, const int32_t* n_ctx,
+                   void* k_ret, void* v_ret, int32_t* ret_pos, int32_t ret_cap, int32_t* out_slot,
+                   void* stream) {
+  kvr::DevDesc d;
+  const int32_t rc = check_desc(desc, d);
+  if (rc != KVR_OK) return rc;
+  if (!k_new || !v_new || !n_ctx || !k_ret || !v_ret || !ret_pos) return KVR_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_ret) || !aligned16(v_ret))
+    return KVR_ERR_INVALID_ARG;
+  if (ret_cap < 1 || ret_cap > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  return finish(kvr::launch_append(d, desc->dtype, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap,
+                                   out_slot, (hipStream_t)stream));
+}
+
+int32_t kvr_select(const kvr_desc* desc, const float* scores, int64_t n_cap, int32_t* ret_pos,
+                   int32_t ret_cap, const int32_t* n_ctx, int32_t n_recent, int32_t k_candidate,
+                   int32_t* evict_slot, int32_t* evict_pos, int32_t* n_evict, int32_t evict_cap,
+                   int32_t* vague_pos, int32_t* n_vague, int32_t vague_cap, void* ws, size_t ws_bytes,
+                   void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  kvr::DevDesc d;
+  const int32_t rc = check_desc(desc, d);
+  if (rc != KVR_OK) return rc;
+  if (!scores || !ret_pos || !n_ctx || !evict_slot || !evict_pos || !n_evict) return KVR_ERR_INVALID_ARG;
+  if ((vague_pos == nullptr) != (n_vague == nullptr)) return KVR_ERR_INVALID_ARG;
+  if (n_cap < 1 || n_cap > MAX_TOKENS || ret_cap < 1 || ret_cap > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  if (n_recent < 0 || k_candidate < 0 || evict_cap < 1) return KVR_ERR_INVALID_ARG;
+  if (vague_pos != nullptr && vague_cap < 1) return KVR_ERR_INVALID_ARG;
+  return finish(kvr::launch_select(d, scores, n_cap, ret_pos, ret_cap, n_ctx, n_recent, k_candidate,
+                                   evict_slot, evict_pos, n_evict, evict_cap, vague_pos, n_vague, vague_cap,
+                                   (hipStream_t)stream));
+}
+
+int32_t kvr_encode(const kvr_desc* desc, const void* k_src, const void* v_src, int32_t src_rows,
+                   const int32_t* src_slot, const int32_t* tok_pos, const int32_t* count, int32_t cap,
+                   void* sketch_k, void* sketch_v, int32_t* out_bucket, uint8_t* out_sign, void* ws,
+                   size_t ws_bytes, void* stream) {
+  kvr::DevDesc d;
+  const int32_t rc = check_desc(desc, d);
+  if (rc != KVR_OK) return rc;
+  if (!k_src || !v_src || !src_slot || !tok_pos || !count || !sketch_k || !sketch_v)
+    return KVR_ERR_INVALID_ARG;
+  if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(sketch_k) || !aligned16(sketch_v))
+    return KVR_ERR_INVALID_ARG;
+  if (src_rows < 1 || src_rows > MAX_TOKENS || cap < 0 || cap > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  const kvr::EncodePlan plan = kvr::encode_plan(d, cap);
+  if (plan.bulk && d.w > 8192) return KVR_ERR_UNSUPPORTED;
+  if (plan.total_bytes > 0) {
+    if (ws == nullptr || !aligned16(ws)) return KVR_ERR_INVALID_ARG;
+    if (ws_bytes < plan.total_bytes) return KVR_ERR_WORKSPACE_TOO_SMALL;
+  }
+  return finish(kvr::launch_encode(d, desc->dtype, k_src, v_src, src_rows, src_slot, tok_pos, count, cap,
+                                   sketch_k, sketch_v, out_bucket, out_sign, ws, plan, (hipStream_t)stream));
+}
+
+int32_t kvr_reconstruct(const kvr_desc* desc, const void* sketch_k, const void* sketch_v,
+                        const int32_t* tok_pos, const int32_t* count, int32_t cap, void* k_out, void* v_out,
+                        void* stream) {
+  kvr::DevDesc d;
+  const int32_t rc = check_desc(desc, d);
+  if (rc != KVR_OK) return rc;
+  if (!sketch_k || !sketch_v || !tok_pos || !count || !k_out || !v_out) return KVR_ERR_INVALID_ARG;
+  if (!aligned16(sketch_k) || !aligned16(sketch_v) || !aligned16(k_out) || !aligned16(v_out))
+    return KVR_ERR_INVALID_ARG;
+  if (cap < 0 || cap > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  return finish(kvr::launch_reconstruct(d, desc->dtype, sketch_k, sketch_v, tok_pos, count, cap, k_out,
+                                        v_out, (hipStream_t)stream));
+}
+
+int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret, const void* v_ret,
+                          const int32_t* ret_pos, int32_t ret_cap, const void* sketch_k,
+                          const void* sketch_v, const int32_t* vague_pos, const int32_t* n_vague,
+                          int32_t vague_cap, float* out, float* scores, int64_t n_cap, void* ws,
+                          size_t ws_bytes, void* stream) {
+  kvr::DevDesc d;
+  const int32_t rc = check_desc(desc, d);
+  if (rc != KVR_OK) return rc;
+  if (!q || !k_ret || !v_ret || !out) return KVR_ERR_INVALID_ARG;
+  if ((vague_pos == nullptr) != (n_vague == nullptr)) return KVR_ERR_INVALID_ARG;
+  if (n_vague != nullptr && (!sketch_k || !sketch_v)) return KVR_ERR_INVALID_ARG;
+  if (ret_cap < 1 || ret_cap > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  if (n_vague == nullptr) vague_cap = 0;
+  if (vague_cap < 0 || vague_cap > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  if (scores != nullptr && (n_cap < 1 || n_cap > MAX_TOKENS)) return KVR_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_ret) || !aligned16(v_ret) || !aligned16(out) ||
+      !aligned16(sketch_k) || !aligned16(sketch_v))
+    return KVR_ERR_INVALID_ARG;
+  const long long tot_cap = (long long)ret_cap + vague_cap;
+  const kvr::AttendPlan plan = kvr::attend_plan(d, tot_cap);
+  if (ws == nullptr || !aligned16(ws)) return KVR_ERR_INVALID_ARG;
+  if (ws_bytes < plan.total_bytes) return KVR_ERR_WORKSPACE_TOO_SMALL;
+  kvr::AttendArgs a;
+  a.q = q;
+  a.k_ret = k_ret;
+  a.v_ret = v_ret;
+  a.ret_pos = ret_pos;
+  a.ret_cap = ret_cap;
+  a.sk = sketch_k;
+  a.sv = sketch_v;
+  a.vague_pos = vague_pos;
+  a.n_vague = n_vague;
+  a.vague_cap = vague_cap;
+  a.out = out;
+  a.scores = scores;
+  a.n_cap = n_cap;
+  char* base = (char*)ws;
+  a.part_o = (float*)(base + plan.off_part_o);
+  a.part_ml = (float*)(base + plan.off_part_ml);
+  a.logits = scores ? (float*)(base + plan.off_logits) : nullptr;
+  a.n_slices = plan.n_slices;
+  a.slice_tokens = plan.slice_tokens;
+  return finish(kvr::launch_attend(d, desc->dtype, a, (hipStream_t)stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,275 @@
+// kvr_attend_decode: cache rebuild (Algorithm 4) fused with decode attention and
+// the accumulation of per-token attention probabilities (Overview, Calculation
+// Phase).  Retained tokens are streamed from their slots, Vague tokens are
+// rebuilt on the fly from the sketch (Algorithm 2) and never written out.
+//
+// Generic path.  A unit's tokens are numbered t = 0 .. ret_cap-1 (retained
+// slots) followed by ret_cap .. ret_cap+n_vague-1 (Vague index list) and cut into
+// slices; one workgroup handles one slice with an online softmax and leaves a
+// partial (max, sum, weighted V) per query head; a second kernel merges the
+// partials, writes `out`, and turns the spilled logits into probabilities that
+// are added to the cumulative scores.
+#include "kvr_launch.h"
+
+namespace kvr {
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+AttendPlan attend_plan(const DevDesc& d, long long tot_cap) {
+  AttendPlan p;
+  const long long units = (long long)d.B * d.Hkv;
+  long long st = (tot_cap * units + 2047) / 2048;
+  st = (st + 63) / 64 * 64;
+  if (st < 64) st = 64;
+  if (st > 1024) st = 1024;
+  p.slice_tokens = (int)st;
+  p.n_slices = (int)((tot_cap + st - 1) / st);
+  if (p.n_slices < 1) p.n_slices = 1;
+  size_t off = 0;
+  p.off_part_o = off;
+  off = align_up(off + (size_t)units * p.n_slices * d.G * D * sizeof(float), 256);
+  p.off_part_ml = off;
+  off = align_up(off + (size_t)units * p.n_slices * d.G * 2 * sizeof(float), 256);
+  p.off_logits = off;
+  off = align_up(off + (size_t)units * (size_t)tot_cap * d.G * sizeof(float), 256);
+  p.total_bytes = off;
+  return p;
+}
+
+template <typename T, int G, int R>
+__global__ __launch_bounds__(256) void attend_main_kernel(DevDesc d, AttendArgs a) {
+  constexpr int VEC = Store<T>::VEC;
+  constexpr int LPT = D / VEC;       // lanes that share one token
+  constexpr int TPW = WAVE / LPT;    // tokens per wave per iteration
+  constexpr int NW = 4;
+  const int unit = blockIdx.y, slice = blockIdx.x;
+  const int b = unit / d.Hkv, hk = unit % d.Hkv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPT, tl = lane / LPT;
+  const int c0 = sub * VEC;
+
+  float qf[G][VEC];
+  {
+    const T* q = (const T*)a.q + ((size_t)b * d.Hq + (size_t)hk * G) * D + c0;
+#pragma unroll
+    for (int g = 0; g < G; ++g) Store<T>::load16(q + (size_t)g * D, qf[g]);
+  }
+  const int nv = a.n_vague ? clampi(a.n_vague[unit], 0, a.vague_cap) : 0;
+  const int tot_cap = a.ret_cap + a.vague_cap;
+  const int total = a.ret_cap + nv;
+  const int t_begin = slice * a.slice_tokens;
+  const int t_end = min(t_begin + a.slice_tokens, total);
+
+  const T* kret = (const T*)a.k_ret + (size_t)unit * a.ret_cap * D;
+  const T* vret = (const T*)a.v_ret + (size_t)unit * a.ret_cap * D;
+  const size_t sk_unit = (size_t)unit * d.r * d.w * D;
+  const T* sk = (const T*)a.sk + sk_unit;
+  const T* sv = (const T*)a.sv + sk_unit;
+  const bool flip_k = (d.sign_mask & 1) != 0, flip_v = (d.sign_mask & 2) != 0;
+
+  float m[G], l[G], acc[G][VEC];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = -__builtin_inff();
+    l[g] = 0.f;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc[g][c] = 0.f;
+  }
+
+  for (int t0 = t_begin + wave * TPW; t0 < t_end; t0 += NW * TPW) {
+    const int t = t0 + tl;
+    bool valid = t < t_end;
+    float kf[VEC], vf[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) { kf[c] = 0.f; vf[c] = 0.f; }
+    if (valid) {
+      if (t < a.ret_cap) {
+        const int pos = a.ret_pos ? a.ret_pos[(size_t)unit * a.ret_cap + t] : t;
+        if (pos < 0) {
+          valid = false;
+        } else {
+          Store<T>::load16(kret + (size_t)t * D + c0, kf);
+          Store<T>::load16(vret + (size_t)t * D + c0, vf);
+        }
+      } else {
+        const int J = a.vague_pos[(size_t)unit * a.vague_cap + (t - a.ret_cap)];
+        query_chunk<T, R>(d, sk, J, c0, flip_k, kf);
+        query_chunk<T, R>(d, sv, J, c0, flip_v, vf);
+      }
+    }
+    float s[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float x = 0.f;
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) x = fmaf(qf[g][c], kf[c], x);
+#pragma unroll
+      for (int off = LPT / 2; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+      s[g] = valid ? x * d.scale : -__builtin_inff();
+    }
+    if (a.logits != nullptr && sub == 0 && t < t_end) {
+      float* lg = a.logits + ((size_t)unit * tot_cap + t) * G;
+#pragma unroll
+      for (int g = 0; g < G; ++g) lg[g] = s[g];
+    }
+    if (valid) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (s[g] > m[g]) {
+          const float corr = expf(m[g] - s[g]);     // exp(-inf) = 0 on the first token
+          m[g] = s[g];
+          l[g] = l[g] * corr + 1.f;
+#pragma unroll
+          for (int c = 0; c < VEC; ++c) acc[g][c] = fmaf(acc[g][c], corr, vf[c]);
+        } else {
+          const float pr = expf(s[g] - m[g]);
+          l[g] += pr;
+#pragma unroll
+          for (int c = 0; c < VEC; ++c) acc[g][c] = fmaf(pr, vf[c], acc[g][c]);
+        }
+      }
+    }
+  }
+
+  // merge the token lane groups of a wave (they hold the same channels)
+#pragma unroll
+  for (int off = LPT; off < WAVE; off <<= 1) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float m2 = __shfl_xor(m[g], off);
+      const float l2 = __shfl_xor(l[g], off);
+      const float mn = fmaxf(m[g], m2);
+      const float e1 = (m[g] == -__builtin_inff()) ? 0.f : expf(m[g] - mn);
+      const float e2 = (m2 == -__builtin_inff()) ? 0.f : expf(m2 - mn);
+      l[g] = l[g] * e1 + l2 * e2;
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) {
+        const float a2 = __shfl_xor(acc[g][c], off);
+        acc[g][c] = acc[g][c] * e1 + a2 * e2;
+      }
+      m[g] = mn;
+    }
+  }
+
+  __shared__ float s_acc[NW][G][D];
+  __shared__ float s_m[NW][G], s_l[NW][G];
+  if (tl == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) s_acc[wave][g][c0 + c] = acc[g][c];
+      if (sub == 0) { s_m[wave][g] = m[g]; s_l[wave][g] = l[g]; }
+    }
+  }
+  __syncthreads();
+  float* po = a.part_o + ((size_t)unit * a.n_slices + slice) * G * D;
+  float* pml = a.part_ml + ((size_t)unit * a.n_slices + slice) * G * 2;
+  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+    const int g = idx / D, c = idx % D;
+    float M = s_m[0][g];
+#pragma unroll
+    for (int w_ = 1; w_ < NW; ++w_) M = fmaxf(M, s_m[w_][g]);
+    float L = 0.f, O = 0.f;
+#pragma unroll
+    for (int w_ = 0; w_ < NW; ++w_) {
+      const float e = (s_m[w_][g] == -__builtin_inff()) ? 0.f : expf(s_m[w_][g] - M);
+      L += s_l[w_][g] * e;
+      O += s_acc[w_][g][c] * e;
+    }
+    po[idx] = O;
+    if (c == 0) { pml[g * 2] = M; pml[g * 2 + 1] = L; }
+  }
+}
+
+template <int G>
+__global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendArgs a) {
+  const int unit = blockIdx.y;
+  const int b = unit / d.Hkv, hk = unit % d.Hkv;
+  __shared__ float sM[G], sL[G];
+  const float* pml = a.part_ml + (size_t)unit * a.n_slices * G * 2;
+  if (threadIdx.x < G) {
+    const int g = threadIdx.x;
+    float M = -__builtin_inff();
+    for (int s = 0; s < a.n_slices; ++s) M = fmaxf(M, pml[(s * G + g) * 2]);
+    float L = 0.f;
+    for (int s = 0; s < a.n_slices; ++s) {
+      const float ms = pml[(s * G + g) * 2], ls = pml[(s * G + g) * 2 + 1];
+      if (ls > 0.f) L += ls * expf(ms - M);
+    }
+    sM[g] = M;
+    sL[g] = L;
+  }
+  __syncthreads();
+  if (blockIdx.x == 0) {
+    const float* po = a.part_o + (size_t)unit * a.n_slices * G * D;
+    for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+      const int g = idx / D;
+      const float M = sM[g], L = sL[g];
+      float o = 0.f;
+      for (int s = 0; s < a.n_slices; ++s) {
+        const float ms = pml[(s * G + g) * 2], ls = pml[(s * G + g) * 2 + 1];
+        if (ls > 0.f) o += po[(size_t)s * G * D + idx] * expf(ms - M);
+      }
+      a.out[((size_t)b * d.Hq + (size_t)hk * G) * D + idx] = (L > 0.f) ? o / L : 0.f;
+    }
+  }
+  if (a.scores != nullptr) {
+    const int nv = a.n_vague ? clampi(a.n_vague[unit], 0, a.vague_cap) : 0;
+    const int tot_cap = a.ret_cap + a.vague_cap;
+    const int total = a.ret_cap + nv;
+    float invL[G], M[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { M[g] = sM[g]; invL[g] = sL[g] > 0.f ? 1.f / sL[g] : 0.f; }
+    float* sc = a.scores + (size_t)unit * a.n_cap;
+    for (int t = blockIdx.x * 256 + threadIdx.x; t < total; t += gridDim.x * 256) {
+      int pos;
+      if (t < a.ret_cap) pos = a.ret_pos ? a.ret_pos[(size_t)unit * a.ret_cap + t] : t;
+      else pos = a.vague_pos[(size_t)unit * a.vague_cap + (t - a.ret_cap)];
+      if (pos < 0 || pos >= a.n_cap) continue;
+      const float* lg = a.logits + ((size_t)unit * tot_cap + t) * G;
+      float p = 0.f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float x = lg[g];
+        if (x != -__builtin_inff()) p += expf(x - M[g]) * invL[g];
+      }
+      sc[pos] += p;
+    }
+  }
+}
+
+template <typename T, int G>
+static void launch_main_r(const DevDesc& d, const AttendArgs& a, dim3 grid, hipStream_t st) {
+  switch (d.r) {
+    case 3: hipLaunchKernelGGL((attend_main_kernel<T, G, 3>), grid, dim3(256), 0, st, d, a); break;
+    case 4: hipLaunchKernelGGL((attend_main_kernel<T, G, 4>), grid, dim3(256), 0, st, d, a); break;
+    default: hipLaunchKernelGGL((attend_main_kernel<T, G, 0>), grid, dim3(256), 0, st, d, a); break;
+  }
+}
+
+template <int G>
+static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st) {
+  const int units = d.B * d.Hkv;
+  dim3 grid(a.n_slices, units);
+  if (dtype == KVR_F32) launch_main_r<float, G>(d, a, grid, st);
+  else launch_main_r<bf16_t, G>(d, a, grid, st);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const long long tot_cap = (long long)a.ret_cap + a.vague_cap;
+  int cx = (int)((tot_cap + 1023) / 1024);
+  if (cx < 1) cx = 1;
+  hipLaunchKernelGGL((attend_combine_kernel<G>), dim3(cx, units), dim3(256), 0, st, d, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st) {
+  switch (d.G) {
+    case 1: return launch_g<1>(d, dtype, a, st);
+    case 2: return launch_g<2>(d, dtype, a, st);
+    case 4: return launch_g<4>(d, dtype, a, st);
+    case 8: return launch_g<8>(d, dtype, a, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace kvr

@@ -1,0 +1,268 @@
+// kvr_encode: batched V.Insert (Vague Sketch, Algorithm 1) without global
+// atomics and with a fixed summation order, so the stored sketch is
+// reproducible bit for bit: every touched slot = round_to_storage(float32(old
+// content) + contributions in list order, added left to right in float32).
+//
+// Two regimes.
+//   small (cap <= 64, the steady state of decode: about one eviction per unit
+//     per step): one workgroup per unit; hashes of the listed tokens go to LDS,
+//     then every (row, channel) thread walks the list and owns the slots it meets
+//     first.
+//   bulk (cap > 64, compressing a prompt): hash all tokens, counting-sort the
+//     token ordinals of each (unit, row) by slot (stable, so list order survives
+//     inside a slot), then one wave per (unit, row, slot) adds its segment
+//     sequentially, lanes across channels.
+#include "kvr_launch.h"
+
+namespace kvr {
+
+constexpr int ENC_SMALL_CAP = 64;
+constexpr int ENC_BULK_MAX_W = 8192;     // LDS cursor array of the sort kernel
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+EncodePlan encode_plan(const DevDesc& d, long long cap) {
+  EncodePlan p;
+  p.bulk = cap > ENC_SMALL_CAP;
+  p.off_bucket = p.off_order = p.off_start = 0;
+  p.total_bytes = 0;
+  if (p.bulk) {
+    const size_t ur = (size_t)d.B * d.Hkv * d.r;
+    size_t off = 0;
+    p.off_bucket = off;
+    off = align_up(off + ur * (size_t)cap * sizeof(int32_t), 256);
+    p.off_order = off;
+    off = align_up(off + ur * (size_t)cap * sizeof(int32_t), 256);
+    p.off_start = off;
+    off = align_up(off + ur * (size_t)(d.w + 1) * sizeof(int32_t), 256);
+    p.total_bytes = off;
+  }
+  return p;
+}
+
+// ------------------------------------------------------------------ small
+template <typename T>
+__global__ __launch_bounds__(D) void encode_small_kernel(
+    DevDesc d, const T* __restrict__ k_src, const T* __restrict__ v_src, int src_rows,
+    const int32_t* __restrict__ src_slot, const int32_t* __restrict__ tok_pos,
+    const int32_t* __restrict__ count, int cap, T* __restrict__ sk, T* __restrict__ sv,
+    int32_t* __restrict__ out_bucket, uint8_t* __restrict__ out_sign) {
+  __shared__ int s_bucket[ENC_SMALL_CAP][KVR_MAX_ROWS];
+  __shared__ int s_slot[ENC_SMALL_CAP];
+  __shared__ unsigned s_sign[ENC_SMALL_CAP];
+  const int unit = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int cnt = clampi(count[unit], 0, min(cap, ENC_SMALL_CAP));
+  if (tid < cnt) {
+    const int J = tok_pos[(size_t)unit * cap + tid];
+    const int slot = src_slot[(size_t)unit * cap + tid];
+    s_slot[tid] = (slot >= 0 && slot < src_rows) ? slot : -1;
+    unsigned sg = 0;
+    for (int i = 0; i < d.r; ++i) {
+      const int bk = bucket_of(d, i, J);
+      s_bucket[tid][i] = bk;
+      if (sign_neg(d, i, J)) sg |= 1u << i;
+      if (out_bucket) out_bucket[((size_t)unit * cap + tid) * d.r + i] = bk;
+    }
+    s_sign[tid] = sg;
+    if (out_sign) out_sign[(size_t)unit * cap + tid] = (uint8_t)sg;
+  }
+  __syncthreads();
+  const int c = tid;   // one channel per thread
+  const bool fk = (d.sign_mask & 1) != 0, fv = (d.sign_mask & 2) != 0;
+  for (int i = 0; i < d.r; ++i) {
+    for (int e = 0; e < cnt; ++e) {
+      if (s_slot[e] < 0) continue;
+      const int bk = s_bucket[e][i];
+      bool first = true;
+      for (int e2 = 0; e2 < e; ++e2) first = first && !(s_slot[e2] >= 0 && s_bucket[e2][i] == bk);
+      if (!first) continue;
+      const size_t idx = (((size_t)unit * d.r + i) * d.w + bk) * D + c;
+      float ak = Store<T>::load1(sk + idx), av = Store<T>::load1(sv + idx);
+      for (int e2 = e; e2 < cnt; ++e2) {
+        if (s_slot[e2] >= 0 && s_bucket[e2][i] == bk) {
+          const bool neg = (s_sign[e2] >> i) & 1u;
+          const size_t src = ((size_t)unit * src_rows + s_slot[e2]) * D + c;
+          const float kv = Store<T>::load1(k_src + src), vv = Store<T>::load1(v_src + src);
+          ak += (fk && neg) ? -kv : kv;
+          av += (fv && neg) ? -vv : vv;
+        }
+      }
+      Store<T>::store1(sk + idx, ak);
+      Store<T>::store1(sv + idx, av);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ bulk
+__global__ __launch_bounds__(256) void encode_hash_kernel(
+    DevDesc d, int src_rows, const int32_t* __restrict__ src_slot, const int32_t* __restrict__ tok_pos,
+    const int32_t* __restrict__ count, int cap, int32_t* __restrict__ ws_bucket,
+    int32_t* __restrict__ out_bucket, uint8_t* __restrict__ out_sign) {
+  const int unit = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  const int cnt = clampi(count[unit], 0, cap);
+  if (e >= cnt) return;
+  const int J = tok_pos[(size_t)unit * cap + e];
+  const int slot = src_slot[(size_t)unit * cap + e];
+  const bool ok = slot >= 0 && slot < src_rows;
+  unsigned sg = 0;
+  for (int i = 0; i < d.r; ++i) {
+    const int bk = bucket_of(d, i, J);
+    ws_bucket[((size_t)unit * d.r + i) * cap + e] = ok ? bk : -1;
+    if (sign_neg(d, i, J)) sg |= 1u << i;
+    if (out_bucket) out_bucket[((size_t)unit * cap + e) * d.r + i] = bk;
+  }
+  if (out_sign) out_sign[(size_t)unit * cap + e] = (uint8_t)sg;
+}
+
+// One wave per (unit, row): stable counting sort of token ordinals by slot.
+__global__ __launch_bounds__(WAVE) void encode_sort_kernel(
+    DevDesc d, const int32_t* __restrict__ count, int cap, const int32_t* __restrict__ ws_bucket,
+    int32_t* __restrict__ ws_order, int32_t* __restrict__ ws_start) {
+  __shared__ int cursor[ENC_BULK_MAX_W];
+  const int ur = blockIdx.x;                 // unit * r + row
+  const int unit = ur / d.r;
+  const int lane = threadIdx.x;
+  const int cnt = clampi(count[unit], 0, cap);
+  const int32_t* bk = ws_bucket + (size_t)ur * cap;
+  int32_t* order = ws_order + (size_t)ur * cap;
+  int32_t* start = ws_start + (size_t)ur * (d.w + 1);
+  for (int s = lane; s < d.w; s += WAVE) cursor[s] = 0;
+  __syncthreads();
+  for (int e = lane; e < cnt; e += WAVE) {
+    const int s = bk[e];
+    if (s >= 0) atomicAdd(&cursor[s], 1);
+  }
+  __syncthreads();
+  int carry = 0;
+  for (int s0 = 0; s0 < d.w; s0 += WAVE) {
+    const int s = s0 + lane;
+    const int c = (s < d.w) ? cursor[s] : 0;
+    int incl = c;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+      const int y = __shfl_up(incl, off);
+      if (lane >= off) incl += y;
+    }
+    const int excl = carry + incl - c;
+    if (s < d.w) { cursor[s] = excl; start[s] = excl; }
+    carry += __shfl(incl, WAVE - 1);
+  }
+  if (lane == 0) start[d.w] = carry;
+  __syncthreads();
+  for (int e0 = 0; e0 < cnt; e0 += WAVE) {
+    const int e = e0 + lane;
+    const int s = (e < cnt) ? bk[e] : -1;
+    int lower = 0;
+    bool higher = false;
+    for (int j = 0; j < WAVE; ++j) {
+      const int sj = __shfl(s, j);
+      const bool same = (sj == s);
+      lower += (same && j < lane) ? 1 : 0;
+      higher = higher || (same && j > lane);
+    }
+    int base = 0;
+    if (s >= 0) base = cursor[s];
+    __syncthreads();
+    if (s >= 0) {
+      order[base + lower] = e;
+      if (!higher) cursor[s] = base + lower + 1;
+    }
+    __syncthreads();
+  }
+}
+
+// One wave per (unit, row, slot): sequential float32 accumulation of the slot's
+// segment, lanes across channels (2 per lane).
+template <typename T>
+__global__ __launch_bounds__(256) void encode_accum_kernel(
+    DevDesc d, const T* __restrict__ k_src, const T* __restrict__ v_src, int src_rows,
+    const int32_t* __restrict__ src_slot, const int32_t* __restrict__ tok_pos, int cap,
+    const int32_t* __restrict__ ws_order, const int32_t* __restrict__ ws_start, T* __restrict__ sk,
+    T* __restrict__ sv) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int s = blockIdx.x * 4 + wave;
+  const int row = blockIdx.y, unit = blockIdx.z;
+  if (s >= d.w) return;
+  const size_t ur = (size_t)unit * d.r + row;
+  const int lo = ws_start[ur * (d.w + 1) + s], hi = ws_start[ur * (d.w + 1) + s + 1];
+  if (hi <= lo) return;
+  const int32_t* order = ws_order + ur * cap;
+  const size_t idx = ((ur * d.w) + s) * D + 2 * lane;
+  float ak0 = Store<T>::load1(sk + idx), ak1 = Store<T>::load1(sk + idx + 1);
+  float av0 = Store<T>::load1(sv + idx), av1 = Store<T>::load1(sv + idx + 1);
+  const bool fk = (d.sign_mask & 1) != 0, fv = (d.sign_mask & 2) != 0;
+  for (int p0 = lo; p0 < hi; p0 += WAVE) {
+    // lanes fetch up to 64 list entries, then the wave walks them in order
+    int my_slot = -1, my_pos = 0;
+    if (p0 + lane < hi) {
+      const int e = order[p0 + lane];
+      my_slot = src_slot[(size_t)unit * cap + e];
+      my_pos = tok_pos[(size_t)unit * cap + e];
+    }
+    const int n = min(WAVE, hi - p0);
+#pragma unroll 4
+    for (int j = 0; j < n; ++j) {
+      const int slot = __shfl(my_slot, j);
+      const int J = __shfl(my_pos, j);
+      const bool neg = sign_neg(d, row, J);
+      const size_t src = ((size_t)unit * src_rows + slot) * D + 2 * lane;
+      const float k0 = Store<T>::load1(k_src + src), k1 = Store<T>::load1(k_src + src + 1);
+      const float v0 = Store<T>::load1(v_src + src), v1 = Store<T>::load1(v_src + src + 1);
+      ak0 += (fk && neg) ? -k0 : k0;
+      ak1 += (fk && neg) ? -k1 : k1;
+      av0 += (fv && neg) ? -v0 : v0;
+      av1 += (fv && neg) ? -v1 : v1;
+    }
+  }
+  Store<T>::store1(sk + idx, ak0);
+  Store<T>::store1(sk + idx + 1, ak1);
+  Store<T>::store1(sv + idx, av0);
+  Store<T>::store1(sv + idx + 1, av1);
+}
+
+template <typename T>
+static hipError_t launch_t(const DevDesc& d, const void* k_src, const void* v_src, int src_rows,
+                           const int32_t* src_slot, const int32_t* tok_pos, const int32_t* count, int cap,
+                           void* sk, void* sv, int32_t* out_bucket, uint8_t* out_sign, void* ws,
+                           const EncodePlan& plan, hipStream_t st) {
+  const int units = d.B * d.Hkv;
+  if (!plan.bulk) {
+    hipLaunchKernelGGL(encode_small_kernel<T>, dim3(units), dim3(D), 0, st, d, (const T*)k_src,
+                       (const T*)v_src, src_rows, src_slot, tok_pos, count, cap, (T*)sk, (T*)sv, out_bucket,
+                       out_sign);
+    return hipGetLastError();
+  }
+  if (d.w > ENC_BULK_MAX_W) return hipErrorInvalidValue;
+  char* base = (char*)ws;
+  int32_t* ws_bucket = (int32_t*)(base + plan.off_bucket);
+  int32_t* ws_order = (int32_t*)(base + plan.off_order);
+  int32_t* ws_start = (int32_t*)(base + plan.off_start);
+  hipLaunchKernelGGL(encode_hash_kernel, dim3((cap + 255) / 256, units), dim3(256), 0, st, d, src_rows,
+                     src_slot, tok_pos, count, cap, ws_bucket, out_bucket, out_sign);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(encode_sort_kernel, dim3(units * d.r), dim3(WAVE), 0, st, d, count, cap, ws_bucket,
+                     ws_order, ws_start);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(encode_accum_kernel<T>, dim3((d.w + 3) / 4, d.r, units), dim3(256), 0, st, d,
+                     (const T*)k_src, (const T*)v_src, src_rows, src_slot, tok_pos, cap, ws_order, ws_start,
+                     (T*)sk, (T*)sv);
+  return hipGetLastError();
+}
+
+hipError_t launch_encode(const DevDesc& d, int dtype, const void* k_src, const void* v_src, int src_rows,
+                         const int32_t* src_slot, const int32_t* tok_pos, const int32_t* count, int cap,
+                         void* sk, void* sv, int32_t* out_bucket, uint8_t* out_sign, void* ws,
+                         const EncodePlan& plan, hipStream_t st) {
+  if (cap <= 0) return hipSuccess;
+  if (dtype == KVR_F32)
+    return launch_t<float>(d, k_src, v_src, src_rows, src_slot, tok_pos, count, cap, sk, sv, out_bucket,
+                           out_sign, ws, plan, st);
+  return launch_t<bf16_t>(d, k_src, v_src, src_rows, src_slot, tok_pos, count, cap, sk, sv, out_bucket,
+                          out_sign, ws, plan, st);
+}
+
+}  // namespace kvr

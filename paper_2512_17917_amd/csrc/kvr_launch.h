@@ -1,0 +1,66 @@
+// Host-side launcher declarations: one per kernel family.  Each launcher
+// receives already validated arguments and returns the hipError_t of its last
+// launch.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "kvr_dev.h"
+
+namespace kvr {
+
+struct AttendArgs {
+  const void* q;
+  const void* k_ret;
+  const void* v_ret;
+  const int32_t* ret_pos;
+  int ret_cap;
+  const void* sk;
+  const void* sv;
+  const int32_t* vague_pos;
+  const int32_t* n_vague;
+  int vague_cap;
+  float* out;
+  float* scores;
+  long long n_cap;
+  // workspace carve-up
+  float* part_o;     // [units, n_slices, G, D]
+  float* part_ml;    // [units, n_slices, G, 2]
+  float* logits;     // [units, ret_cap + vague_cap, G] or nullptr when scores == nullptr
+  int n_slices;
+  int slice_tokens;
+};
+
+struct AttendPlan {
+  int slice_tokens;
+  int n_slices;
+  size_t off_part_o, off_part_ml, off_logits, total_bytes;
+};
+AttendPlan attend_plan(const DevDesc& d, long long tot_cap);
+
+struct EncodePlan {
+  bool bulk;
+  size_t off_bucket, off_order, off_start, total_bytes;
+};
+EncodePlan encode_plan(const DevDesc& d, long long cap);
+
+hipError_t launch_reconstruct(const DevDesc& d, int dtype, const void* sk, const void* sv,
+                              const int32_t* tok_pos, const int32_t* count, int cap,
+                              void* k_out, void* v_out, hipStream_t st);
+
+hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st);
+
+hipError_t launch_select(const DevDesc& d, const float* scores, long long n_cap, int32_t* ret_pos,
+                         int ret_cap, const int32_t* n_ctx, int n_recent, int k_candidate,
+                         int32_t* evict_slot, int32_t* evict_pos, int32_t* n_evict, int evict_cap,
+                         int32_t* vague_pos, int32_t* n_vague, int vague_cap, hipStream_t st);
+
+hipError_t launch_append(const DevDesc& d, int dtype, const void* k_new, const void* v_new,
+                         const int32_t* n_ctx, void* k_ret, void* v_ret, int32_t* ret_pos, int ret_cap,
+                         int32_t* out_slot, hipStream_t st);
+
+hipError_t launch_encode(const DevDesc& d, int dtype, const void* k_src, const void* v_src, int src_rows,
+                         const int32_t* src_slot, const int32_t* tok_pos, const int32_t* count, int cap,
+                         void* sk, void* sv, int32_t* out_bucket, uint8_t* out_sign,
+                         void* ws, const EncodePlan& plan, hipStream_t st);
+
+}  // namespace kvr
