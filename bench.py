@@ -1,0 +1,289 @@
+#!/usr/bin/env python3
+"""Benchmark of the KVReviver decode hot path on one MI355X.
+
+A "step" is one decode step of the whole path for every layer of the workload:
+per layer  kvr_append -> kvr_select -> kvr_encode -> kvr_attend_decode  on all
+(sequence, kv head) units, layers one after another on one stream.  Inputs are
+synthetic (kvr_synth) and resident in HBM before the timed region.
+
+Prints ONE JSON line: decode steps/s, achieved algorithmic HBM bandwidth, the
+roofline object of the dominant kernel (main attention kernel, timed live with
+HIP events on the launch stream) and the CPU oracle timed on a bounded sample.
+
+    python bench.py [--workload c4] [--steps K] [--warmup W] [--gpus 1]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes_per_unit(wl, n_ctx):
+    """Bytes one unit must move per decode step, by definition: retained K and V,
+    the K and V sketch, the Vague index list, the cumulative scores (read and
+    write) and q / out.  Nothing an implementation adds (partials, spills,
+    re-reads) is counted."""
+    e = 4 if wl.dtype == "f32" else 2
+    D, G = wl.head_dim, wl.group
+    R, S = wl.n_retained, wl.sketch_slots
+    a = n_ctx - R
+    return 2 * R * D * e + 2 * S * D * e + 4 * a + 8 * n_ctx + 2 * G * D * e
+
+
+class HipEvents:
+    """Raw HIP events (the library records them around its main kernel)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self):
+        ev = C.c_void_p()
+        rc = self.hip.hipEventCreate(C.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        return ev
+
+    def elapsed_ms(self, a, b):
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return ms.value
+
+
+def cpu_baseline(wl, n_units, budget_s=20.0):
+    """Time the oracle's decode step on host cores for a few units of the same
+    workload (full shape), scale to the whole job."""
+    import numpy as np
+    import kvr_synth as S
+    from oracle import kvr_oracle as O
+
+    scale = 1.0 / math.sqrt(wl.head_dim)
+    G = wl.group
+    layer = 0
+    params = O.hash_params_from_seed(S.BASE_SEED + layer, wl.r)
+    q0, q1 = S.queries(wl, layer, 0), S.queries(wl, layer, 1)
+    kn, vn = S.new_tokens(wl, layer, 0)
+    f64 = lambda t: t.to("cpu").double().numpy()
+    times, used = [], []
+    t_start = time.perf_counter()
+    for u in range(n_units):
+        b, h = divmod(u, wl.n_kv_heads)
+        if b >= wl.batch:
+            break
+        K, V = S.kv_unit(wl, layer, b, h)
+        st = O.dense_prefill_state(f64(K), f64(V), f64(q0[b, h * G:(h + 1) * G]), scale, wl.r, wl.w, params,
+                                   wl.dtype, n_recent=wl.n_recent, k_candidate=wl.n_candidate,
+                                   n_cap=wl.context + 2, acc_dtype=np.float32)
+        st.compress()
+        st = O.compact(st, wl.n_retained + 1)
+        t0 = time.perf_counter()
+        st.decode_step(f64(kn[b, h]), f64(vn[b, h]), f64(q1[b, h * G:(h + 1) * G]), scale)
+        times.append(time.perf_counter() - t0)
+        used.append((b, h))
+        if time.perf_counter() - t_start > budget_s:
+            break
+    per_unit = sum(times) / len(times)
+    total_units = wl.layers * wl.units_per_layer
+    return {
+        "value": 1.0 / (per_unit * total_units),
+        "unit": "decode steps/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"{len(times)} unit(s) (layer 0, sequence/head {used[0]}..{used[-1]}) x 1 decode step at full "
+                  f"shape, {per_unit:.3f} s per unit-step, scaled by {total_units} units per step",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--layers", type=int, default=None, help="debug: run fewer layers (result is then not the named workload)")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-units", type=int, default=8)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 1 GiB device copies (reference for scaling profiler byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import kvr_synth as S
+    from paper_2512_17917_amd import binding as kvr
+    from paper_2512_17917_amd.state import LayerState
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    kvr.lib()                                  # fails loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = S.WORKLOADS[args.workload]
+    L = wl.layers if args.layers is None else args.layers
+    K_steps = args.steps if args.steps is not None else min(wl.steps, 128)
+    W = args.warmup
+    T = K_steps + W
+    B, Hkv, Hq, D = wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.head_dim
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    log(f"[bench] workload {wl.name}: {L} layers x {B} seq x {Hkv} kv heads, N={wl.context}, r={wl.r}, w={wl.w}, "
+        f"R={wl.n_retained}, a0={wl.n_vague0}; {W} warmup + {K_steps} timed steps")
+
+    # ---- build the compressed state of every layer (not timed as steps) ---------
+    descs, layers = [], []
+    n_ctx = torch.zeros(B, dtype=torch.int32, device=dev)
+    ws_att = ws_enc = None
+    knew, vnew, qs = [], [], []
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_compress_ms = 0.0
+    t_setup = time.perf_counter()
+    for l in range(L):
+        params = kvr.kvr_hash_params_from_seed(S.BASE_SEED + l, wl.r)
+        d = kvr.make_desc(B, Hq, Hkv, wl.r, wl.w, wl.torch_dtype, hash_params=params)
+        Kf, Vf = S.kv_layer(wl, l, device=dev)
+        qall = S.queries_many(wl, l, 0, T + 1, device=dev)          # q[0] initialises the scores
+        ls, _ = LayerState.from_prefill(d, Kf, Vf, qall[0].contiguous(), n_recent=wl.n_recent,
+                                        k_candidate=wl.n_candidate, max_new_tokens=T, ws_attend=ws_att,
+                                        ws_encode=ws_enc, n_ctx=n_ctx, timers=(ev0, ev1))
+        torch.cuda.synchronize()
+        t_compress_ms += ev0.elapsed_time(ev1)
+        ne = ls.n_evict.min().item()
+        if ne != wl.n_vague0 or ls.n_evict.max().item() != wl.n_vague0:
+            raise RuntimeError(f"layer {l}: prompt compression evicted {ne}, expected {wl.n_vague0}")
+        ws_att, ws_enc = ls.ws_attend, ls.ws_encode
+        del Kf, Vf
+        kn, vn = S.kv_layer(wl, l, wl.context, wl.context + T, device=dev)      # [B, Hkv, T, D]
+        knew.append(kn.permute(2, 0, 1, 3).contiguous())
+        vnew.append(vn.permute(2, 0, 1, 3).contiguous())
+        qs.append(qall[1:].contiguous())
+        descs.append(d)
+        layers.append(ls)
+        if l == 0 or (l + 1) % 12 == 0:
+            log(f"[bench] layer {l + 1}/{L} compressed ({time.perf_counter() - t_setup:.1f} s)")
+    torch.cuda.empty_cache()
+
+    def run_step(t):
+        n_ctx.add_(1)
+        for l in range(L):
+            layers[l].decode_step(knew[l][t], vnew[l][t], qs[l][t], bump_n_ctx=False)
+
+    for t in range(W):
+        run_step(t)
+    torch.cuda.synchronize()
+
+    # ---- timed region ----------------------------------------------------------
+    hev = HipEvents()
+    pairs = [(hev.create(), hev.create()) for _ in range(K_steps * L)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    i = 0
+    for t in range(W, T):
+        n_ctx.add_(1)
+        for l in range(L):
+            a, b = pairs[i]
+            i += 1
+            kvr.kvr_profile_events(a, b)
+            layers[l].decode_step(knew[l][t], vnew[l][t], qs[l][t], bump_n_ctx=False)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    kern_ms = [hev.elapsed_ms(a, b) for a, b in pairs]
+    for a, b in pairs:
+        hev.hip.hipEventDestroy(a)
+        hev.hip.hipEventDestroy(b)
+
+    # sanity of the state after the run: one eviction per unit per step
+    nv = layers[0].n_vague
+    if nv.min().item() != wl.n_vague0 + T or nv.max().item() != wl.n_vague0 + T:
+        raise RuntimeError("bookkeeping drifted: n_vague is not a0 + steps")
+    if not torch.isfinite(layers[-1].out).all():
+        raise RuntimeError("non-finite attention output")
+
+    steps_per_s = K_steps / elapsed
+    n_mid = wl.context + W + (K_steps + 1) // 2
+    bytes_unit = algorithmic_bytes_per_unit(wl, n_mid)
+    bytes_launch = bytes_unit * wl.units_per_layer
+    bytes_step = bytes_launch * L
+    avg_kern_s = (sum(kern_ms) / len(kern_ms)) * 1e-3
+    achieved = bytes_launch / avg_kern_s / 1e9
+    result = {
+        "metric": "decode steps/sec (encode+reconstruct+attend, all layers) + achieved HBM GB/s",
+        "value": steps_per_s,
+        "unit": "decode steps/s",
+        "n_gpus": 1,
+        "steps": K_steps,
+        "warmup": W,
+        "ms_per_step": 1e3 * elapsed / K_steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {L} layers, batch {B}, {Hq} q / {Hkv} kv heads, head_dim {D}, "
+                               f"context {wl.context}, budget {wl.budget}, sketch r={wl.r} w={wl.w}, "
+                               f"retained {wl.n_retained}, vague {wl.n_vague0}+t",
+                   "global_batch": B, "seq_len": wl.context, "parallelism": "1 GPU"},
+        "achieved_hbm_gbs": bytes_step * steps_per_s / 1e9,
+        "hbm_frac_whole_step": bytes_step * steps_per_s / 1e9 / HBM_PEAK_GBS,
+        "algorithmic_bytes_per_step": bytes_step,
+        "tokens_per_s": steps_per_s * B,
+        "prompt_compress_ms_total": t_compress_ms,
+        "roofline": {
+            "kernel": "attend_main_kernel (one launch = one layer, all units)",
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "algorithmic_bytes_per_launch": bytes_launch,
+            "avg_launch_ms": avg_kern_s * 1e3,
+            "launches_timed": len(kern_ms),
+        },
+    }
+    if args.layers is not None and args.layers != wl.layers:
+        result["config"]["workload"] += f" [DEBUG: only {L} of {wl.layers} layers]"
+    log(f"[bench] {steps_per_s:.2f} steps/s, {result['ms_per_step']:.3f} ms/step, "
+        f"{result['achieved_hbm_gbs']:.0f} GB/s algorithmic ({100 * result['hbm_frac_whole_step']:.1f}% of HBM peak); "
+        f"main kernel {avg_kern_s * 1e6:.1f} us/launch -> {achieved:.0f} GB/s")
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    if args.skip_cpu_baseline:
+        result["cpu_baseline"] = None
+    else:
+        del layers, knew, vnew, qs
+        torch.cuda.empty_cache()
+        torch.set_num_threads(1)
+        result["cpu_baseline"] = cpu_baseline(wl, args.cpu_units)
+        log(f"[bench] oracle: {result['cpu_baseline']['value']:.3e} steps/s ({result['cpu_baseline']['sample']})")
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

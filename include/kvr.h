@@ -105,6 +105,15 @@ const char* kvr_version(void);
 int32_t kvr_last_hip_error(void);
 
 /*
+ * Profiling aid.  Arms a pair of hipEvent_t (passed as void*, created by the
+ * caller with timing enabled) for the calling thread: the next
+ * kvr_attend_decode call records `start` on its stream right before its main
+ * kernel (the one that streams the retained tokens and rebuilds the Vague
+ * ones) and `stop` right after it, then disarms them.  NULL, NULL disarms.
+ */
+int32_t kvr_profile_events(void* start, void* stop);
+
+/*
  * Fill out[r][4] (host) from a seed: a 64-bit LCG x <- x*6364136223846793005 +
  * 1442695040888963407 (mod 2^64), x0 = seed, is stepped once per word; rows in
  * order, words in the order a, b, c, d; a and c are then made odd.  Pure host code.

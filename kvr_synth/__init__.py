@@ -23,6 +23,7 @@ is used or reproduced.
 """
 from __future__ import annotations
 
+import functools
 import math
 from dataclasses import dataclass
 
@@ -195,6 +196,7 @@ def uniforms(keys, count: int, offset: int = 0, device="cpu") -> torch.Tensor:
 # ---------------------------------------------------------------------------
 # per-unit small quantities (always computed on the CPU, float64)
 # ---------------------------------------------------------------------------
+@functools.lru_cache(maxsize=None)
 def topic_direction(wl: Workload, layer: int, b: int, h: int) -> np.ndarray:
     """Unit vector u of the (layer, sequence, kv head) unit, float64 [D]."""
     g = normals([stream_key(BASE_SEED, wl.cfg_id, _T_U, layer, b, h)], wl.head_dim)

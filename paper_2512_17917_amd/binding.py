@@ -29,7 +29,7 @@ _ERR_NAMES = {-1: "KVR_ERR_INVALID_ARG", -2: "KVR_ERR_UNSUPPORTED",
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvr.so")
 
-EXPORTS = ["kvr_version", "kvr_last_hip_error", "kvr_hash_params_from_seed", "kvr_hash_host",
+EXPORTS = ["kvr_version", "kvr_last_hip_error", "kvr_profile_events", "kvr_hash_params_from_seed", "kvr_hash_host",
            "kvr_workspace_size", "kvr_append", "kvr_select", "kvr_encode", "kvr_reconstruct",
            "kvr_attend_decode"]
 
@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
         L.kvr_version.argtypes = []
         L.kvr_last_hip_error.restype = i32
         L.kvr_last_hip_error.argtypes = []
+        L.kvr_profile_events.restype = i32
+        L.kvr_profile_events.argtypes = [vp, vp]
         L.kvr_hash_params_from_seed.restype = i32
         L.kvr_hash_params_from_seed.argtypes = [C.c_uint64, i32, C.POINTER(C.c_uint64)]
         L.kvr_hash_host.restype = i32
@@ -156,6 +158,11 @@ def _ws(ws):
 # ---------------------------------------------------------------------------
 def kvr_version() -> str:
     return lib().kvr_version().decode()
+
+
+def kvr_profile_events(start, stop):
+    """start, stop: raw hipEvent_t handles (ints) or None."""
+    _check("kvr_profile_events", lib().kvr_profile_events(start, stop))
 
 
 def kvr_hash_params_from_seed(seed: int, r: int):

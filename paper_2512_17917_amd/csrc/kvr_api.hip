@@ -8,6 +8,7 @@
 namespace {
 
 thread_local int32_t g_last_hip_error = 0;
+thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 constexpr uint64_t LCG_MUL = 6364136223846793005ull;
 constexpr uint64_t LCG_INC = 1442695040888963407ull;
@@ -57,6 +58,12 @@ extern "C" {
 const char* kvr_version(void) { return "kvr 0.1 (gfx950)"; }
 
 int32_t kvr_last_hip_error(void) { return g_last_hip_error; }
+
+int32_t kvr_profile_events(void* start, void* stop) {
+  g_ev_start = (hipEvent_t)start;
+  g_ev_stop = (hipEvent_t)stop;
+  return KVR_OK;
+}
 
 int32_t kvr_hash_params_from_seed(uint64_t seed, int32_t r, uint64_t* out) {
   if (out == nullptr || r < 1 || r > KVR_MAX_ROWS) return KVR_ERR_INVALID_ARG;
@@ -217,7 +224,9 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret
   a.logits = scores ? (float*)(base + plan.off_logits) : nullptr;
   a.n_slices = plan.n_slices;
   a.slice_tokens = plan.slice_tokens;
-  return finish(kvr::launch_attend(d, desc->dtype, a, (hipStream_t)stream));
+  const hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;
+  g_ev_start = g_ev_stop = nullptr;
+  return finish(kvr::launch_attend(d, desc->dtype, a, (hipStream_t)stream, e0, e1));
 }
 
 }  // extern "C"

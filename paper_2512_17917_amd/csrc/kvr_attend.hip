@@ -248,12 +248,15 @@ static void launch_main_r(const DevDesc& d, const AttendArgs& a, dim3 grid, hipS
 }
 
 template <int G>
-static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st) {
+static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st,
+                           hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int units = d.B * d.Hkv;
   dim3 grid(a.n_slices, units);
+  if (ev_start) (void)hipEventRecord(ev_start, st);
   if (dtype == KVR_F32) launch_main_r<float, G>(d, a, grid, st);
   else launch_main_r<bf16_t, G>(d, a, grid, st);
   hipError_t e = hipGetLastError();
+  if (ev_stop) (void)hipEventRecord(ev_stop, st);
   if (e != hipSuccess) return e;
   const long long tot_cap = (long long)a.ret_cap + a.vague_cap;
   int cx = (int)((tot_cap + 1023) / 1024);
@@ -262,12 +265,13 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a, hip
   return hipGetLastError();
 }
 
-hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st) {
+hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st,
+                         hipEvent_t ev_start, hipEvent_t ev_stop) {
   switch (d.G) {
-    case 1: return launch_g<1>(d, dtype, a, st);
-    case 2: return launch_g<2>(d, dtype, a, st);
-    case 4: return launch_g<4>(d, dtype, a, st);
-    case 8: return launch_g<8>(d, dtype, a, st);
+    case 1: return launch_g<1>(d, dtype, a, st, ev_start, ev_stop);
+    case 2: return launch_g<2>(d, dtype, a, st, ev_start, ev_stop);
+    case 4: return launch_g<4>(d, dtype, a, st, ev_start, ev_stop);
+    case 8: return launch_g<8>(d, dtype, a, st, ev_start, ev_stop);
     default: return hipErrorInvalidValue;
   }
 }

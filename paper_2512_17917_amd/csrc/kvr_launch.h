@@ -47,7 +47,10 @@ hipError_t launch_reconstruct(const DevDesc& d, int dtype, const void* sk, const
                               const int32_t* tok_pos, const int32_t* count, int cap,
                               void* k_out, void* v_out, hipStream_t st);
 
-hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st);
+// ev_start / ev_stop (may be null): recorded on `st` right before and right after
+// the main kernel, for profiling.
+hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st,
+                         hipEvent_t ev_start, hipEvent_t ev_stop);
 
 hipError_t launch_select(const DevDesc& d, const float* scores, long long n_cap, int32_t* ret_pos,
                          int ret_cap, const int32_t* n_ctx, int n_recent, int k_candidate,

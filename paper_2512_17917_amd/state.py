@@ -14,7 +14,7 @@ class LayerState:
     """All per-unit buffers of one layer, unit-major [B, Hkv, ...]."""
 
     def __init__(self, desc, *, n_recent, k_candidate, ret_cap, vague_cap, n_cap, evict_cap=8,
-                 device="cuda"):
+                 device="cuda", ws_attend=None, ws_encode=None, n_ctx=None):
         self.desc = desc
         self.n_recent, self.k_candidate = int(n_recent), int(k_candidate)
         self.ret_cap, self.vague_cap, self.n_cap, self.evict_cap = int(ret_cap), int(vague_cap), int(n_cap), int(evict_cap)
@@ -33,10 +33,14 @@ class LayerState:
         self.evict_slot = torch.zeros(B, Hkv, self.evict_cap, dtype=torch.int32, device=dev)
         self.evict_pos = torch.zeros(B, Hkv, self.evict_cap, dtype=torch.int32, device=dev)
         self.n_evict = torch.zeros(B, Hkv, dtype=torch.int32, device=dev)
-        self.n_ctx = torch.zeros(B, dtype=torch.int32, device=dev)
+        # several layers may share one n_ctx tensor and one workspace (calls on one
+        # stream are ordered, and no workspace content outlives a call)
+        self.n_ctx = torch.zeros(B, dtype=torch.int32, device=dev) if n_ctx is None else n_ctx
         self.out = torch.zeros(B, Hq, D, dtype=torch.float32, device=dev)
-        self.ws_attend = kvr.alloc_workspace(desc, kvr.KVR_OP_ATTEND, self.ret_cap + self.vague_cap, dev)
-        self.ws_encode = kvr.alloc_workspace(desc, kvr.KVR_OP_ENCODE, self.evict_cap, dev)
+        self.ws_attend = ws_attend if ws_attend is not None else kvr.alloc_workspace(
+            desc, kvr.KVR_OP_ATTEND, self.ret_cap + self.vague_cap, dev)
+        self.ws_encode = ws_encode if ws_encode is not None else kvr.alloc_workspace(
+            desc, kvr.KVR_OP_ENCODE, self.evict_cap, dev)
 
     # -- the four calls of a decode step, on this layer's buffers ---------------
     def append(self, k_new, v_new):
@@ -74,7 +78,7 @@ class LayerState:
     # -- building the state from a prompt ---------------------------------------
     @classmethod
     def from_prefill(cls, desc, K, V, q0, *, n_recent, k_candidate, max_new_tokens, evict_cap=8,
-                     init_scores=None):
+                     init_scores=None, ws_attend=None, ws_encode=None, n_ctx=None, timers=None):
         """Compress a prompt's KV cache K, V [B, Hkv, N, D]: cumulative scores are
         initialised with one dense attention pass of q0 (or taken from
         init_scores [B, Hkv, N]), the Recent and Candidate parts are kept raw and
@@ -88,7 +92,8 @@ class LayerState:
         n_vague0 = max(N - R, 0)
         vague_cap = n_vague0 + max_new_tokens
         st = cls(desc, n_recent=n_recent, k_candidate=k_candidate, ret_cap=ret_cap, vague_cap=vague_cap,
-                 n_cap=n_cap, evict_cap=evict_cap, device=dev)
+                 n_cap=n_cap, evict_cap=evict_cap, device=dev, ws_attend=ws_attend, ws_encode=ws_encode,
+                 n_ctx=n_ctx)
         st.n_ctx.fill_(N)
         # 1. cumulative scores of the prompt
         if init_scores is not None:
@@ -103,12 +108,16 @@ class LayerState:
         ev_cap = max(n_vague0, 1)
         ev_slot = torch.zeros(B, Hkv, ev_cap, dtype=torch.int32, device=dev)
         ev_pos = torch.zeros(B, Hkv, ev_cap, dtype=torch.int32, device=dev)
+        ws = kvr.alloc_workspace(desc, kvr.KVR_OP_ENCODE, ev_cap, dev)
+        if timers is not None:       # (start, stop) torch events around select + bulk encode
+            timers[0].record()
         kvr.kvr_select(desc, st.scores, n_cap, full_pos, N, st.n_ctx, n_recent, k_candidate,
                        ev_slot, ev_pos, st.n_evict, ev_cap, st.vague_pos, st.n_vague, vague_cap)
         # 3. bulk insert of the evicted tokens
-        ws = kvr.alloc_workspace(desc, kvr.KVR_OP_ENCODE, ev_cap, dev)
         kvr.kvr_encode(desc, K, V, N, ev_slot, ev_pos, st.n_evict, ev_cap, st.sketch_k, st.sketch_v,
                        None, None, ws)
+        if timers is not None:
+            timers[1].record()
         del ws
         # 4. compact the kept rows (ascending slot order) into the small slot array
         kept_first = torch.sort((full_pos < 0).to(torch.int8), dim=2, stable=True).indices[:, :, :R]
