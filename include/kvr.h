@@ -107,9 +107,10 @@ int32_t kvr_last_hip_error(void);
 /*
  * Profiling aid.  Arms a pair of hipEvent_t (passed as void*, created by the
  * caller with timing enabled) for the calling thread: the next
- * kvr_attend_decode call records `start` on its stream right before its main
- * kernel (the one that streams the retained tokens and rebuilds the Vague
- * ones) and `stop` right after it, then disarms them.  NULL, NULL disarms.
+ * kvr_attend_decode call records `start` on its stream right before its first
+ * kernel and `stop` right after the last kernel that touches token data (the
+ * ones that stream the retained tokens and rebuild the Vague ones; the final
+ * merge kernel is outside), then disarms them.  NULL, NULL disarms.
  */
 int32_t kvr_profile_events(void* start, void* stop);
 
@@ -127,11 +128,12 @@ int32_t kvr_hash_params_from_seed(uint64_t seed, int32_t r, uint64_t* out);
 int32_t kvr_hash_host(const kvr_desc* desc, int32_t J, int32_t* bucket, int32_t* sign);
 
 /*
- * Bytes of workspace a call of kind `op` needs.  n_max: SELECT -> ret_cap;
- * ENCODE -> cap; RECONSTRUCT -> cap (always 0 bytes); ATTEND -> ret_cap +
- * vague_cap.  Pure host code.
+ * Bytes of workspace a call of kind `op` needs for the capacities it will be
+ * given: SELECT (n_a = ret_cap, n_b ignored; 0 bytes), ENCODE (n_a = cap),
+ * RECONSTRUCT (n_a = cap; 0 bytes), ATTEND (n_a = ret_cap, n_b = vague_cap; use
+ * n_b = 0 for calls without a Vague list).  Pure host code.
  */
-int32_t kvr_workspace_size(const kvr_desc* desc, int32_t op, int64_t n_max, size_t* bytes);
+int32_t kvr_workspace_size(const kvr_desc* desc, int32_t op, int64_t n_a, int64_t n_b, size_t* bytes);
 
 /*
  * Push one newly generated token per unit into the Recent part (Algorithm 3,
@@ -192,7 +194,7 @@ int32_t kvr_select(const kvr_desc* desc, const float* scores, int64_t n_cap,
  *   sketch_k, sketch_v  dev [B, Hkv, r, w, D] storage type, read and written
  *   out_bucket  dev int32 [B, Hkv, cap, r] or NULL: h_i(J) of every listed token
  *   out_sign    dev uint8 [B, Hkv, cap] or NULL: bit i set iff g_i(J) = -1
- *   ws          per kvr_workspace_size(KVR_OP_ENCODE, cap)
+ *   ws          per kvr_workspace_size(KVR_OP_ENCODE, cap, 0)
  */
 int32_t kvr_encode(const kvr_desc* desc, const void* k_src, const void* v_src, int32_t src_rows,
                    const int32_t* src_slot, const int32_t* tok_pos, const int32_t* count, int32_t cap,
@@ -231,7 +233,7 @@ int32_t kvr_reconstruct(const kvr_desc* desc, const void* sketch_k, const void* 
  *   out        dev float32 [B, Hq, D], written
  *   scores     dev float32 [B, Hkv, n_cap] read and written, or NULL; positions
  *              >= n_cap are not accumulated
- *   ws         per kvr_workspace_size(KVR_OP_ATTEND, ret_cap + vague_cap)
+ *   ws         per kvr_workspace_size(KVR_OP_ATTEND, ret_cap, vague_cap)
  */
 int32_t kvr_attend_decode(const kvr_desc* desc, const void* q,
                           const void* k_ret, const void* v_ret, const int32_t* ret_pos, int32_t ret_cap,

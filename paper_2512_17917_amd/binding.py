@@ -72,7 +72,7 @@ def lib() -> C.CDLL:
         L.kvr_hash_host.restype = i32
         L.kvr_hash_host.argtypes = [dp, i32, C.POINTER(i32), C.POINTER(i32)]
         L.kvr_workspace_size.restype = i32
-        L.kvr_workspace_size.argtypes = [dp, i32, i64, C.POINTER(sz)]
+        L.kvr_workspace_size.argtypes = [dp, i32, i64, i64, C.POINTER(sz)]
         L.kvr_append.restype = i32
         L.kvr_append.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
         L.kvr_select.restype = i32
@@ -178,14 +178,14 @@ def kvr_hash_host(desc: kvr_desc, J: int):
     return [int(b[i]) for i in range(desc.r)], [int(s[i]) for i in range(desc.r)]
 
 
-def kvr_workspace_size(desc: kvr_desc, op: int, n_max: int) -> int:
+def kvr_workspace_size(desc: kvr_desc, op: int, n_a: int, n_b: int = 0) -> int:
     out = C.c_size_t(0)
-    _check("kvr_workspace_size", lib().kvr_workspace_size(C.byref(desc), op, n_max, C.byref(out)))
+    _check("kvr_workspace_size", lib().kvr_workspace_size(C.byref(desc), op, n_a, n_b, C.byref(out)))
     return int(out.value)
 
 
-def alloc_workspace(desc: kvr_desc, op: int, n_max: int, device="cuda") -> torch.Tensor:
-    n = kvr_workspace_size(desc, op, n_max)
+def alloc_workspace(desc: kvr_desc, op: int, n_a: int, n_b: int = 0, device="cuda") -> torch.Tensor:
+    n = kvr_workspace_size(desc, op, n_a, n_b)
     return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
 
 

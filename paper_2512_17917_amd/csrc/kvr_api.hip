@@ -91,21 +91,21 @@ int32_t kvr_hash_host(const kvr_desc* desc, int32_t J, int32_t* bucket, int32_t*
   return KVR_OK;
 }
 
-int32_t kvr_workspace_size(const kvr_desc* desc, int32_t op, int64_t n_max, size_t* bytes) {
+int32_t kvr_workspace_size(const kvr_desc* desc, int32_t op, int64_t n_a, int64_t n_b, size_t* bytes) {
   kvr::DevDesc d;
   const int32_t rc = check_desc(desc, d);
   if (rc != KVR_OK) return rc;
-  if (bytes == nullptr || n_max < 0 || n_max > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  if (bytes == nullptr || n_a < 0 || n_a > MAX_TOKENS || n_b < 0 || n_b > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
   switch (op) {
     case KVR_OP_SELECT:
     case KVR_OP_RECONSTRUCT:
       *bytes = 0;
       return KVR_OK;
     case KVR_OP_ENCODE:
-      *bytes = kvr::encode_plan(d, n_max).total_bytes;
+      *bytes = kvr::encode_plan(d, n_a).total_bytes;
       return KVR_OK;
     case KVR_OP_ATTEND:
-      *bytes = kvr::attend_plan(d, n_max).total_bytes;
+      *bytes = kvr::attend_plan(d, desc->dtype, n_a, n_b).total_bytes;
       return KVR_OK;
     default:
       return KVR_ERR_INVALID_ARG;
@@ -200,8 +200,7 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret
   if (!aligned16(q) || !aligned16(k_ret) || !aligned16(v_ret) || !aligned16(out) ||
       !aligned16(sketch_k) || !aligned16(sketch_v))
     return KVR_ERR_INVALID_ARG;
-  const long long tot_cap = (long long)ret_cap + vague_cap;
-  const kvr::AttendPlan plan = kvr::attend_plan(d, tot_cap);
+  const kvr::AttendPlan plan = kvr::attend_plan(d, desc->dtype, ret_cap, vague_cap);
   if (ws == nullptr || !aligned16(ws)) return KVR_ERR_INVALID_ARG;
   if (ws_bytes < plan.total_bytes) return KVR_ERR_WORKSPACE_TOO_SMALL;
   kvr::AttendArgs a;
@@ -222,11 +221,9 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret
   a.part_o = (float*)(base + plan.off_part_o);
   a.part_ml = (float*)(base + plan.off_part_ml);
   a.logits = scores ? (float*)(base + plan.off_logits) : nullptr;
-  a.n_slices = plan.n_slices;
-  a.slice_tokens = plan.slice_tokens;
   const hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;
   g_ev_start = g_ev_stop = nullptr;
-  return finish(kvr::launch_attend(d, desc->dtype, a, (hipStream_t)stream, e0, e1));
+  return finish(kvr::launch_attend(d, desc->dtype, a, plan, (hipStream_t)stream, e0, e1));
 }
 
 }  // extern "C"

@@ -3,28 +3,78 @@
 // Phase).  Retained tokens are streamed from their slots, Vague tokens are
 // rebuilt on the fly from the sketch (Algorithm 2) and never written out.
 //
-// Generic path.  A unit's tokens are numbered t = 0 .. ret_cap-1 (retained
-// slots) followed by ret_cap .. ret_cap+n_vague-1 (Vague index list) and cut into
-// slices; one workgroup handles one slice with an online softmax and leaves a
-// partial (max, sum, weighted V) per query head; a second kernel merges the
-// partials, writes `out`, and turns the spilled logits into probabilities that
-// are added to the cumulative scores.
+// A unit's tokens are numbered t = 0 .. ret_cap-1 (retained slots) followed by
+// ret_cap .. ret_cap+n_vague-1 (Vague index list) and cut into slices; every
+// slice leaves a partial (max, sum, weighted V) per query head, and the merge
+// kernel combines the partials, writes `out`, and turns the spilled logits into
+// probabilities that are added to the cumulative scores.
+//
+// This file: the plan, the generic slice kernel (any storage type, any r, any
+// sign setting; Vague rows gathered straight from global memory), the merge
+// kernel and the dispatch.  The LDS-staged kernel for the Vague list is in
+// kvr_attend_staged.hip.
 #include "kvr_launch.h"
 
 namespace kvr {
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-AttendPlan attend_plan(const DevDesc& d, long long tot_cap) {
-  AttendPlan p;
-  const long long units = (long long)d.B * d.Hkv;
-  long long st = (tot_cap * units + 2047) / 2048;
+constexpr int STAGED_KMAX = 6;                    // wave-rounds (64 tokens) per wave, staged kernel
+constexpr int STAGED_LDS_LIMIT = 160 * 1024;      // LDS per workgroup on gfx950
+
+static int slice_tokens_for(long long tokens, long long units) {
+  long long st = (tokens * units + 2047) / 2048;
   st = (st + 63) / 64 * 64;
   if (st < 64) st = 64;
   if (st > 1024) st = 1024;
-  p.slice_tokens = (int)st;
-  p.n_slices = (int)((tot_cap + st - 1) / st);
-  if (p.n_slices < 1) p.n_slices = 1;
+  return (int)st;
+}
+
+AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long vague_cap) {
+  AttendPlan p;
+  const long long units = (long long)d.B * d.Hkv;
+  const long long tot_cap = ret_cap + vague_cap;
+  p.staged = false;
+  p.n_vslices = 0;
+  p.ch = 0;
+  p.lds_bytes = 0;
+  // staged kernel: bf16, the paper's sign setting, G <= 4, r = 3 or 4, bucket fits 15 bits
+  if (dtype == KVR_BF16 && d.sign_mask == 2 && d.G <= 4 && (d.r == 3 || d.r == 4) && d.w <= 32768 &&
+      vague_cap >= 64) {
+    const int fixed = STAGED_KMAX * 512 * 8 + 8 * d.G * 64 * 4 + 1024 + d.G * 256;
+    int ch = 0;
+    for (int c = 64; c >= 8; c >>= 1) {
+      if ((long long)d.r * d.w * c * 2 + fixed + 64 <= STAGED_LDS_LIMIT) { ch = c; break; }
+    }
+    if (ch) {
+      const long long wr = (vague_cap + 63) / 64;          // wave-rounds to cover the list
+      double best = 1e30;
+      int best_rho = 1, best_n = 1;
+      for (int rho = 1; rho <= STAGED_KMAX; ++rho) {
+        const long long n = (wr + 8 * rho - 1) / (8 * rho);
+        const double util = (double)wr / (double)(n * 8 * rho);
+        const double wgs = (double)(units * n);
+        const double quant = (double)((units * n + 255) / 256) / (wgs / 256.0);
+        const double cost = ((rho + 1.0) / rho) / util * (wgs >= 256 ? quant : 1.0);
+        if (cost < best) { best = cost; best_rho = rho; best_n = (int)n; }
+      }
+      (void)best_rho;
+      p.staged = true;
+      p.ch = ch;
+      p.n_vslices = best_n;
+      p.lds_bytes = (int)align_up((size_t)d.r * d.w * ch * 2, 16) + fixed;
+    }
+  }
+  if (p.staged) {
+    p.rslice_tokens = slice_tokens_for(ret_cap, units);
+    p.n_rslices = (int)((ret_cap + p.rslice_tokens - 1) / p.rslice_tokens);
+    p.n_slices = p.n_rslices + p.n_vslices;
+  } else {
+    p.rslice_tokens = slice_tokens_for(tot_cap, units);
+    p.n_rslices = (int)((tot_cap + p.rslice_tokens - 1) / p.rslice_tokens);
+    if (p.n_rslices < 1) p.n_rslices = 1;
+    p.n_slices = p.n_rslices;
+  }
   size_t off = 0;
   p.off_part_o = off;
   off = align_up(off + (size_t)units * p.n_slices * d.G * D * sizeof(float), 256);
@@ -36,6 +86,9 @@ AttendPlan attend_plan(const DevDesc& d, long long tot_cap) {
   return p;
 }
 
+// ---------------------------------------------------------------------------
+// generic slice kernel
+// ---------------------------------------------------------------------------
 template <typename T, int G, int R>
 __global__ __launch_bounds__(256) void attend_main_kernel(DevDesc d, AttendArgs a) {
   constexpr int VEC = Store<T>::VEC;
@@ -56,7 +109,7 @@ __global__ __launch_bounds__(256) void attend_main_kernel(DevDesc d, AttendArgs 
   }
   const int nv = a.n_vague ? clampi(a.n_vague[unit], 0, a.vague_cap) : 0;
   const int tot_cap = a.ret_cap + a.vague_cap;
-  const int total = a.ret_cap + nv;
+  const int total = min(a.ret_cap + nv, a.tok_limit);
   const int t_begin = slice * a.slice_tokens;
   const int t_end = min(t_begin + a.slice_tokens, total);
 
@@ -181,34 +234,66 @@ __global__ __launch_bounds__(256) void attend_main_kernel(DevDesc d, AttendArgs 
   }
 }
 
+// ---------------------------------------------------------------------------
+// merge kernel
+// ---------------------------------------------------------------------------
+constexpr int CMB_MAXW = 2048;     // slice weights kept in LDS when n_slices * G fits
+
 template <int G>
 __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendArgs a) {
   const int unit = blockIdx.y;
   const int b = unit / d.Hkv, hk = unit % d.Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   __shared__ float sM[G], sL[G];
+  __shared__ float sW[CMB_MAXW];
   const float* pml = a.part_ml + (size_t)unit * a.n_slices * G * 2;
-  if (threadIdx.x < G) {
-    const int g = threadIdx.x;
-    float M = -__builtin_inff();
-    for (int s = 0; s < a.n_slices; ++s) M = fmaxf(M, pml[(s * G + g) * 2]);
-    float L = 0.f;
-    for (int s = 0; s < a.n_slices; ++s) {
+  const bool w_in_lds = a.n_slices * G <= CMB_MAXW;
+  // global max and sum per head: wave w takes heads w, w + 4
+  for (int g = wave; g < G; g += 4) {
+    float M = -__builtin_inff(), L = 0.f;
+    for (int s = lane; s < a.n_slices; s += WAVE) {
       const float ms = pml[(s * G + g) * 2], ls = pml[(s * G + g) * 2 + 1];
-      if (ls > 0.f) L += ls * expf(ms - M);
+      if (ls > 0.f) {
+        const float mn = fmaxf(M, ms);
+        L = L * expf(M - mn) + ls * expf(ms - mn);
+        M = mn;
+      }
     }
-    sM[g] = M;
-    sL[g] = L;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+      const float M2 = __shfl_xor(M, off), L2 = __shfl_xor(L, off);
+      const float mn = fmaxf(M, M2);
+      const float e1 = (M == -__builtin_inff()) ? 0.f : expf(M - mn);
+      const float e2 = (M2 == -__builtin_inff()) ? 0.f : expf(M2 - mn);
+      L = L * e1 + L2 * e2;
+      M = mn;
+    }
+    if (lane == 0) { sM[g] = M; sL[g] = L; }
   }
   __syncthreads();
   if (blockIdx.x == 0) {
+    if (w_in_lds) {
+      for (int idx = tid; idx < a.n_slices * G; idx += 256) {
+        const int g = idx % G;
+        const float ms = pml[idx * 2], ls = pml[idx * 2 + 1];
+        sW[idx] = (ls > 0.f) ? expf(ms - sM[g]) : 0.f;
+      }
+      __syncthreads();
+    }
     const float* po = a.part_o + (size_t)unit * a.n_slices * G * D;
-    for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+    for (int idx = tid; idx < G * D; idx += 256) {
       const int g = idx / D;
       const float M = sM[g], L = sL[g];
       float o = 0.f;
       for (int s = 0; s < a.n_slices; ++s) {
-        const float ms = pml[(s * G + g) * 2], ls = pml[(s * G + g) * 2 + 1];
-        if (ls > 0.f) o += po[(size_t)s * G * D + idx] * expf(ms - M);
+        float wgt;
+        if (w_in_lds) {
+          wgt = sW[s * G + g];
+        } else {
+          const float ms = pml[(s * G + g) * 2], ls = pml[(s * G + g) * 2 + 1];
+          wgt = (ls > 0.f) ? expf(ms - M) : 0.f;
+        }
+        o = fmaf(po[(size_t)s * G * D + idx], wgt, o);
       }
       a.out[((size_t)b * d.Hq + (size_t)hk * G) * D + idx] = (L > 0.f) ? o / L : 0.f;
     }
@@ -221,7 +306,7 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
 #pragma unroll
     for (int g = 0; g < G; ++g) { M[g] = sM[g]; invL[g] = sL[g] > 0.f ? 1.f / sL[g] : 0.f; }
     float* sc = a.scores + (size_t)unit * a.n_cap;
-    for (int t = blockIdx.x * 256 + threadIdx.x; t < total; t += gridDim.x * 256) {
+    for (int t = blockIdx.x * 256 + tid; t < total; t += gridDim.x * 256) {
       int pos;
       if (t < a.ret_cap) pos = a.ret_pos ? a.ret_pos[(size_t)unit * a.ret_cap + t] : t;
       else pos = a.vague_pos[(size_t)unit * a.vague_cap + (t - a.ret_cap)];
@@ -238,6 +323,7 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
   }
 }
 
+// ---------------------------------------------------------------------------
 template <typename T, int G>
 static void launch_main_r(const DevDesc& d, const AttendArgs& a, dim3 grid, hipStream_t st) {
   switch (d.r) {
@@ -248,14 +334,21 @@ static void launch_main_r(const DevDesc& d, const AttendArgs& a, dim3 grid, hipS
 }
 
 template <int G>
-static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st,
-                           hipEvent_t ev_start, hipEvent_t ev_stop) {
+static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, const AttendPlan& plan,
+                           hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int units = d.B * d.Hkv;
-  dim3 grid(a.n_slices, units);
+  AttendArgs a = a0;
+  a.n_slices = plan.n_slices;
+  a.slice_tokens = plan.rslice_tokens;
+  a.n_rslices = plan.n_rslices;
+  a.n_vslices = plan.n_vslices;
+  a.tok_limit = plan.staged ? a.ret_cap : a.ret_cap + a.vague_cap;
   if (ev_start) (void)hipEventRecord(ev_start, st);
+  dim3 grid(plan.n_rslices, units);
   if (dtype == KVR_F32) launch_main_r<float, G>(d, a, grid, st);
   else launch_main_r<bf16_t, G>(d, a, grid, st);
   hipError_t e = hipGetLastError();
+  if (e == hipSuccess && plan.staged) e = launch_attend_vague_staged(d, a, plan, st);
   if (ev_stop) (void)hipEventRecord(ev_stop, st);
   if (e != hipSuccess) return e;
   const long long tot_cap = (long long)a.ret_cap + a.vague_cap;
@@ -265,13 +358,13 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a, hip
   return hipGetLastError();
 }
 
-hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st,
-                         hipEvent_t ev_start, hipEvent_t ev_stop) {
+hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, const AttendPlan& plan,
+                         hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   switch (d.G) {
-    case 1: return launch_g<1>(d, dtype, a, st, ev_start, ev_stop);
-    case 2: return launch_g<2>(d, dtype, a, st, ev_start, ev_stop);
-    case 4: return launch_g<4>(d, dtype, a, st, ev_start, ev_stop);
-    case 8: return launch_g<8>(d, dtype, a, st, ev_start, ev_stop);
+    case 1: return launch_g<1>(d, dtype, a, plan, st, ev_start, ev_stop);
+    case 2: return launch_g<2>(d, dtype, a, plan, st, ev_start, ev_stop);
+    case 4: return launch_g<4>(d, dtype, a, plan, st, ev_start, ev_stop);
+    case 8: return launch_g<8>(d, dtype, a, plan, st, ev_start, ev_stop);
     default: return hipErrorInvalidValue;
   }
 }

@@ -8,6 +8,20 @@
 
 namespace kvr {
 
+// How one kvr_attend_decode call is cut into workgroups.  Slices 0 .. n_rslices-1
+// cover the retained slots, slices n_rslices .. n_slices-1 the Vague index list.
+struct AttendPlan {
+  bool staged;          // Vague tokens by the LDS-staged kernel (else the generic kernel does everything)
+  int n_slices;         // partial results per unit
+  int n_rslices;        // of which: retained slices
+  int rslice_tokens;    // tokens per retained (or, generic path, any) slice
+  int n_vslices;        // staged: workgroups per unit over the Vague list
+  int ch;               // staged: channels per LDS phase
+  int lds_bytes;        // staged: dynamic LDS per workgroup
+  size_t off_part_o, off_part_ml, off_logits, total_bytes;
+};
+AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long vague_cap);
+
 struct AttendArgs {
   const void* q;
   const void* k_ret;
@@ -26,16 +40,12 @@ struct AttendArgs {
   float* part_o;     // [units, n_slices, G, D]
   float* part_ml;    // [units, n_slices, G, 2]
   float* logits;     // [units, ret_cap + vague_cap, G] or nullptr when scores == nullptr
-  int n_slices;
-  int slice_tokens;
+  int n_slices;      // partial results per unit (all kinds)
+  int slice_tokens;  // generic kernel: tokens per slice
+  int tok_limit;     // generic kernel: it handles tokens t < min(tok_limit, ret_cap + n_vague)
+  int n_rslices;     // staged kernel: index of its first partial
+  int n_vslices;     // staged kernel: workgroups per unit
 };
-
-struct AttendPlan {
-  int slice_tokens;
-  int n_slices;
-  size_t off_part_o, off_part_ml, off_logits, total_bytes;
-};
-AttendPlan attend_plan(const DevDesc& d, long long tot_cap);
 
 struct EncodePlan {
   bool bulk;
@@ -47,10 +57,15 @@ hipError_t launch_reconstruct(const DevDesc& d, int dtype, const void* sk, const
                               const int32_t* tok_pos, const int32_t* count, int cap,
                               void* k_out, void* v_out, hipStream_t st);
 
-// ev_start / ev_stop (may be null): recorded on `st` right before and right after
-// the main kernel, for profiling.
-hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, hipStream_t st,
-                         hipEvent_t ev_start, hipEvent_t ev_stop);
+// ev_start / ev_stop (may be null): recorded on `st` right before the first and
+// right after the last kernel that touches token data (everything except the
+// merge kernel), for profiling.
+hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, const AttendPlan& plan,
+                         hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
+
+// Staged kernel over the Vague list (bf16, values signed only, G <= 4, r in {3,4}).
+hipError_t launch_attend_vague_staged(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
+                                      hipStream_t st);
 
 hipError_t launch_select(const DevDesc& d, const float* scores, long long n_cap, int32_t* ret_pos,
                          int ret_cap, const int32_t* n_ctx, int n_recent, int k_candidate,

@@ -4,20 +4,41 @@
 // One workgroup per unit.  Every eligible slot gets a 64-bit key
 //   (order-preserving image of its float32 score) << 32 | ~position
 // so that "higher score first, then lower position" is plain integer order and
-// all keys are distinct.  The k-th largest key is found by an 8-pass radix
-// select on LDS histograms; the slots below it are emitted in ascending slot
-// order with a block-wide prefix sum.
+// all keys are distinct.  The slots to evict are the n_e = eligible - k lowest
+// keys.  Two ways to find the cut:
+//   - n_e small (the decode steady state evicts one token per unit per step):
+//     n_e rounds of a block-wide minimum over keys above the previous minimum;
+//   - otherwise an 8-pass radix select of the k-th largest key on LDS histograms
+//     whose 256 bins are scanned by 256 threads.
+// Up to 8192 slots the keys are computed once and stay in registers (8 per
+// thread); larger slot arrays (a whole prompt) recompute them from memory in
+// every pass.  The evicted slots are emitted in ascending slot order with a
+// ballot / prefix-sum compaction.
 #include "kvr_launch.h"
 
 namespace kvr {
 
 constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / WAVE;
+constexpr int SEL_KPT = 8;                       // keys per thread held in registers
+constexpr int SEL_REG_SLOTS = SEL_THREADS * SEL_KPT;
+constexpr int SEL_SMALL = 8;                     // up to this many evictions: repeated minimum
+constexpr unsigned long long KEY_NONE = ~0ull;   // no valid key is all ones (position bits would be ~pos of pos = 0 with score image all ones = NaN)
+
+struct SelShared {
+  unsigned hist[256];
+  unsigned long long wmin[SEL_WAVES];
+  unsigned long long prefix;
+  int wsum[SEL_WAVES];
+  int wscan[4];
+  int krem, cnt, base;
+};
 
 __device__ __forceinline__ bool slot_key(const int32_t* __restrict__ rp, const float* __restrict__ sc,
                                          int slot, int ret_cap, int recent_from, long long n_cap,
-                                         unsigned long long& key, int& pos) {
+                                         unsigned long long& key) {
   if (slot >= ret_cap) return false;
-  pos = rp[slot];
+  const int pos = rp[slot];
   if (pos < 0 || pos >= recent_from || pos >= n_cap) return false;
   uint32_t b = __float_as_uint(sc[pos]);
   if (b == 0x80000000u) b = 0u;                                   // -0 ranks as +0
@@ -26,6 +47,61 @@ __device__ __forceinline__ bool slot_key(const int32_t* __restrict__ rp, const f
   return true;
 }
 
+__device__ __forceinline__ int key_pos(unsigned long long key) { return (int)(~(uint32_t)key); }
+
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int m) {
+  const uint32_t lo = __shfl_xor((int)(uint32_t)v, m), hi = __shfl_xor((int)(uint32_t)(v >> 32), m);
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+// Block-wide minimum of one value per thread (KEY_NONE = nothing).
+__device__ __forceinline__ unsigned long long block_min(unsigned long long v, SelShared& sh) {
+#pragma unroll
+  for (int m = 1; m < WAVE; m <<= 1) {
+    const unsigned long long o = shfl_xor_u64(v, m);
+    v = o < v ? o : v;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();                       // wmin may still be read from the previous round
+  if (lane == 0) sh.wmin[wave] = v;
+  __syncthreads();
+  unsigned long long r = sh.wmin[0];
+#pragma unroll
+  for (int w_ = 1; w_ < SEL_WAVES; ++w_) r = sh.wmin[w_] < r ? sh.wmin[w_] : r;
+  return r;
+}
+
+// 256 bins, scanned from the top: pick the bin where the running count reaches
+// krem; updates sh.krem and ors the digit into sh.prefix.  All threads call it.
+__device__ __forceinline__ void pick_digit(SelShared& sh, int byte) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int c = 0, incl = 0;
+  if (tid < 256) {
+    c = (int)sh.hist[255 - tid];
+    incl = c;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+      const int y = __shfl_up(incl, off);
+      if (lane >= off) incl += y;
+    }
+    if (lane == WAVE - 1) sh.wscan[wave] = incl;
+  }
+  __syncthreads();
+  if (tid < 256) {
+    int before = 0;
+#pragma unroll
+    for (int w_ = 0; w_ < 4; ++w_) before += (w_ < wave) ? sh.wscan[w_] : 0;
+    incl += before;
+    const int krem = sh.krem;
+    if (incl >= krem && incl - c < krem) {          // exactly one thread
+      sh.krem = krem - (incl - c);
+      sh.prefix |= (unsigned long long)(255 - tid) << (8 * byte);
+    }
+  }
+  __syncthreads();
+}
+
+template <bool REG>
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     DevDesc d, const float* __restrict__ scores, long long n_cap, int32_t* __restrict__ ret_pos,
     int ret_cap, const int32_t* __restrict__ n_ctx, int n_recent, int k_cand,
@@ -34,28 +110,47 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
   const int unit = blockIdx.x;
   const int b = unit / d.Hkv;
   const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   int32_t* rp = ret_pos + (size_t)unit * ret_cap;
   const float* sc = scores + (size_t)unit * n_cap;
   const int recent_from = n_ctx[b] - n_recent;
   if (k_cand < 0) k_cand = 0;
+  __shared__ SelShared sh;
 
-  __shared__ unsigned hist[256];
-  __shared__ unsigned long long s_prefix;
-  __shared__ int s_krem, s_cnt, s_base;
-  __shared__ int s_wsum[SEL_THREADS / WAVE];
+  // keys of this thread's slots: slot = j * SEL_THREADS + tid
+  unsigned long long rkey[REG ? SEL_KPT : 1];
+  const int n_chunks = (ret_cap + SEL_THREADS - 1) / SEL_THREADS;
+  auto get_key = [&](int j, unsigned long long& key) -> bool {
+    if constexpr (REG) {
+      key = rkey[j];
+      return key != KEY_NONE;
+    } else {
+      return slot_key(rp, sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key);
+    }
+  };
 
-  if (tid == 0) { s_cnt = 0; s_base = 0; s_prefix = 0ull; s_krem = k_cand; }
+  if (tid == 0) { sh.cnt = 0; sh.base = 0; sh.prefix = 0ull; sh.krem = k_cand; }
   __syncthreads();
   {
     int c = 0;
-    for (int slot = tid; slot < ret_cap; slot += SEL_THREADS) {
-      unsigned long long key; int pos;
-      c += slot_key(rp, sc, slot, ret_cap, recent_from, n_cap, key, pos) ? 1 : 0;
+    if constexpr (REG) {
+#pragma unroll
+      for (int j = 0; j < SEL_KPT; ++j) {
+        unsigned long long key = KEY_NONE;
+        const bool ok = slot_key(rp, sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key);
+        rkey[j] = ok ? key : KEY_NONE;
+        c += ok ? 1 : 0;
+      }
+    } else {
+      for (int j = 0; j < n_chunks; ++j) {
+        unsigned long long key;
+        c += get_key(j, key) ? 1 : 0;
+      }
     }
-    if (c) atomicAdd(&s_cnt, c);
+    if (c) atomicAdd(&sh.cnt, c);
   }
   __syncthreads();
-  const int n_e = s_cnt - k_cand;
+  const int n_e = sh.cnt - k_cand;
   if (n_e <= 0) {
     if (tid == 0) n_evict[unit] = 0;
     return;
@@ -66,65 +161,72 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     return;
   }
 
-  const bool evict_all = (k_cand == 0);
-  if (!evict_all) {
-    for (int byte = 7; byte >= 0; --byte) {
-      if (tid < 256) hist[tid] = 0u;
-      __syncthreads();
-      const unsigned long long prefix = s_prefix;
-      for (int slot = tid; slot < ret_cap; slot += SEL_THREADS) {
-        unsigned long long key; int pos;
-        if (slot_key(rp, sc, slot, ret_cap, recent_from, n_cap, key, pos)) {
-          const bool match = (byte == 7) || ((key >> (8 * (byte + 1))) == (prefix >> (8 * (byte + 1))));
-          if (match) atomicAdd(&hist[(unsigned)(key >> (8 * byte)) & 255u], 1u);
-        }
+  // cut: evict every eligible key <= cut
+  unsigned long long cut;
+  if (k_cand == 0) {
+    cut = KEY_NONE - 1;
+  } else if (REG && n_e <= SEL_SMALL) {
+    unsigned long long last = 0;
+    bool have = false;
+    for (int it = 0; it < n_e; ++it) {
+      unsigned long long mine = KEY_NONE;
+#pragma unroll
+      for (int j = 0; j < (REG ? SEL_KPT : 1); ++j) {
+        const unsigned long long key = rkey[j];
+        if (key != KEY_NONE && (!have || key > last) && key < mine) mine = key;
       }
-      __syncthreads();
-      if (tid == 0) {
-        int krem = s_krem;
-        unsigned cum = 0;
-        for (int dg = 255; dg >= 0; --dg) {
-          const unsigned c = hist[dg];
-          if (cum + c >= (unsigned)krem) {
-            s_krem = krem - (int)cum;
-            s_prefix = prefix | ((unsigned long long)dg << (8 * byte));
-            break;
-          }
-          cum += c;
-        }
-      }
-      __syncthreads();
+      last = block_min(mine, sh);
+      have = true;
     }
+    cut = last;
+  } else {
+    for (int byte = 7; byte >= 0; --byte) {
+      if (tid < 256) sh.hist[tid] = 0u;
+      __syncthreads();
+      const unsigned long long prefix = sh.prefix;
+#pragma unroll
+      for (int j = 0; j < (REG ? SEL_KPT : n_chunks); ++j) {
+        unsigned long long key;
+        if (get_key(j, key)) {
+          const bool match = (byte == 7) || ((key >> (8 * (byte + 1))) == (prefix >> (8 * (byte + 1))));
+          if (match) atomicAdd(&sh.hist[(unsigned)(key >> (8 * byte)) & 255u], 1u);
+        }
+      }
+      __syncthreads();
+      pick_digit(sh, byte);
+    }
+    cut = sh.prefix - 1;       // prefix = the k-th largest key; it stays
   }
-  const unsigned long long T = s_prefix;   // the k-th largest key (unused when evict_all)
 
-  const int lane = tid & 63, wave = tid >> 6;
-  for (int chunk0 = 0; chunk0 < ret_cap; chunk0 += SEL_THREADS) {
-    const int slot = chunk0 + tid;
-    unsigned long long key = 0; int pos = -1;
-    bool flag = slot_key(rp, sc, slot, ret_cap, recent_from, n_cap, key, pos);
-    flag = flag && (evict_all || key < T);
+#pragma unroll
+  for (int j = 0; j < (REG ? SEL_KPT : n_chunks); ++j) {
+    if (REG && j >= n_chunks) break;
+    const int slot = j * SEL_THREADS + tid;
+    unsigned long long key = 0;
+    bool flag = get_key(j, key);
+    flag = flag && key <= cut;
     const unsigned long long bal = __ballot(flag);
     const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) s_wsum[wave] = __popcll(bal);
+    if (lane == 0) sh.wsum[wave] = __popcll(bal);
     __syncthreads();
     int before = 0, tot = 0;
 #pragma unroll
-    for (int w_ = 0; w_ < SEL_THREADS / WAVE; ++w_) {
-      const int c = s_wsum[w_];
+    for (int w_ = 0; w_ < SEL_WAVES; ++w_) {
+      const int c = sh.wsum[w_];
       before += (w_ < wave) ? c : 0;
       tot += c;
     }
-    const int base = s_base;
+    const int base = sh.base;
     if (flag) {
       const int idx = base + before + in_wave;      // < n_e <= evict_cap
+      const int pos = key_pos(key);
       evict_slot[(size_t)unit * evict_cap + idx] = slot;
       evict_pos[(size_t)unit * evict_cap + idx] = pos;
       rp[slot] = -1;
       if (vague_pos && n_vague) vague_pos[(size_t)unit * vague_cap + nv_old + idx] = pos;
     }
     __syncthreads();
-    if (tid == 0) s_base = base + tot;
+    if (tid == 0) sh.base = base + tot;
     __syncthreads();
   }
   if (tid == 0) {
@@ -137,9 +239,14 @@ hipError_t launch_select(const DevDesc& d, const float* scores, long long n_cap,
                          int ret_cap, const int32_t* n_ctx, int n_recent, int k_candidate,
                          int32_t* evict_slot, int32_t* evict_pos, int32_t* n_evict, int evict_cap,
                          int32_t* vague_pos, int32_t* n_vague, int vague_cap, hipStream_t st) {
-  hipLaunchKernelGGL(select_kernel, dim3(d.B * d.Hkv), dim3(SEL_THREADS), 0, st, d, scores, n_cap, ret_pos,
-                     ret_cap, n_ctx, n_recent, k_candidate, evict_slot, evict_pos, n_evict, evict_cap,
-                     vague_pos, n_vague, vague_cap);
+  if (ret_cap <= SEL_REG_SLOTS)
+    hipLaunchKernelGGL(select_kernel<true>, dim3(d.B * d.Hkv), dim3(SEL_THREADS), 0, st, d, scores, n_cap,
+                       ret_pos, ret_cap, n_ctx, n_recent, k_candidate, evict_slot, evict_pos, n_evict,
+                       evict_cap, vague_pos, n_vague, vague_cap);
+  else
+    hipLaunchKernelGGL(select_kernel<false>, dim3(d.B * d.Hkv), dim3(SEL_THREADS), 0, st, d, scores, n_cap,
+                       ret_pos, ret_cap, n_ctx, n_recent, k_candidate, evict_slot, evict_pos, n_evict,
+                       evict_cap, vague_pos, n_vague, vague_cap);
   return hipGetLastError();
 }
 
@@ -159,9 +266,18 @@ __global__ __launch_bounds__(256) void append_kernel(DevDesc d, const T* __restr
   if (tid == 0) s_free = 0x7fffffff;
   __syncthreads();
   int mine = 0x7fffffff;
-  for (int s0 = 0; s0 < ret_cap; s0 += 256) {       // lowest empty slot
-    const int s = s0 + tid;
-    if (s < ret_cap && rp[s] < 0) { mine = s; break; }
+  for (int s0 = 0; s0 < ret_cap; s0 += 256 * 8) {       // lowest empty slot, 8 independent loads a round
+    int p[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = s0 + u * 256 + tid;
+      p[u] = (s < ret_cap) ? rp[s] : 0;
+    }
+#pragma unroll
+    for (int u = 7; u >= 0; --u) {
+      const int s = s0 + u * 256 + tid;
+      if (s < ret_cap && p[u] < 0 && s < mine) mine = s;
+    }
   }
   if (mine != 0x7fffffff) atomicMin(&s_free, mine);
   __syncthreads();

@@ -38,9 +38,9 @@ class LayerState:
         self.n_ctx = torch.zeros(B, dtype=torch.int32, device=dev) if n_ctx is None else n_ctx
         self.out = torch.zeros(B, Hq, D, dtype=torch.float32, device=dev)
         self.ws_attend = ws_attend if ws_attend is not None else kvr.alloc_workspace(
-            desc, kvr.KVR_OP_ATTEND, self.ret_cap + self.vague_cap, dev)
+            desc, kvr.KVR_OP_ATTEND, self.ret_cap, self.vague_cap, dev)
         self.ws_encode = ws_encode if ws_encode is not None else kvr.alloc_workspace(
-            desc, kvr.KVR_OP_ENCODE, self.evict_cap, dev)
+            desc, kvr.KVR_OP_ENCODE, self.evict_cap, 0, dev)
 
     # -- the four calls of a decode step, on this layer's buffers ---------------
     def append(self, k_new, v_new):
@@ -99,7 +99,7 @@ class LayerState:
         if init_scores is not None:
             st.scores[:, :, :N] = init_scores
         else:
-            ws = kvr.alloc_workspace(desc, kvr.KVR_OP_ATTEND, N, dev)
+            ws = kvr.alloc_workspace(desc, kvr.KVR_OP_ATTEND, N, 0, dev)
             kvr.kvr_attend_decode(desc, q0, K, V, None, N, None, None, None, None, 0, st.out, st.scores,
                                   n_cap, ws)
             del ws
@@ -108,7 +108,7 @@ class LayerState:
         ev_cap = max(n_vague0, 1)
         ev_slot = torch.zeros(B, Hkv, ev_cap, dtype=torch.int32, device=dev)
         ev_pos = torch.zeros(B, Hkv, ev_cap, dtype=torch.int32, device=dev)
-        ws = kvr.alloc_workspace(desc, kvr.KVR_OP_ENCODE, ev_cap, dev)
+        ws = kvr.alloc_workspace(desc, kvr.KVR_OP_ENCODE, ev_cap, 0, dev)
         if timers is not None:       # (start, stop) torch events around select + bulk encode
             timers[0].record()
         kvr.kvr_select(desc, st.scores, n_cap, full_pos, N, st.n_ctx, n_recent, k_candidate,

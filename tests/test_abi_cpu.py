@@ -59,14 +59,14 @@ def test_workspace_sizes():
     assert kvr.kvr_workspace_size(d, kvr.KVR_OP_ENCODE, 8) == 0
     big = kvr.kvr_workspace_size(d, kvr.KVR_OP_ENCODE, 30000)
     assert big >= 16 * 8 * 3 * 2 * 30000 * 4
-    a1 = kvr.kvr_workspace_size(d, kvr.KVR_OP_ATTEND, 1000)
-    a2 = kvr.kvr_workspace_size(d, kvr.KVR_OP_ATTEND, 33000)
+    a1 = kvr.kvr_workspace_size(d, kvr.KVR_OP_ATTEND, 200, 800)
+    a2 = kvr.kvr_workspace_size(d, kvr.KVR_OP_ATTEND, 7400, 25600)
     assert 0 < a1 < a2
     assert a2 >= 16 * 8 * 33000 * 4 * 4           # the spilled logits
     with pytest.raises(kvr.KvrError):
         kvr.kvr_workspace_size(d, 99, 10)
     with pytest.raises(kvr.KvrError):
-        kvr.kvr_workspace_size(d, kvr.KVR_OP_ATTEND, -1)
+        kvr.kvr_workspace_size(d, kvr.KVR_OP_ATTEND, -1, 0)
 
 
 def bad_descs():
@@ -98,11 +98,11 @@ def test_bad_descriptors_are_rejected_without_a_gpu():
     L = kvr.lib()
     sz = C.c_size_t(0)
     for d, k, v, code in bad_descs():
-        assert L.kvr_workspace_size(C.byref(d), kvr.KVR_OP_ATTEND, 100, C.byref(sz)) == code, (k, v)
+        assert L.kvr_workspace_size(C.byref(d), kvr.KVR_OP_ATTEND, 100, 0, C.byref(sz)) == code, (k, v)
         # a compute entry point with otherwise plausible (fake, never dereferenced) pointers
         p = 0x10000
         assert L.kvr_reconstruct(C.byref(d), p, p, p, p, 4, p, p, None) == code, (k, v)
-    assert L.kvr_workspace_size(None, kvr.KVR_OP_ATTEND, 100, C.byref(sz)) == kvr.KVR_ERR_INVALID_ARG
+    assert L.kvr_workspace_size(None, kvr.KVR_OP_ATTEND, 100, 0, C.byref(sz)) == kvr.KVR_ERR_INVALID_ARG
 
 
 def test_bad_arguments_are_rejected_without_a_gpu():

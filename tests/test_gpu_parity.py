@@ -304,7 +304,7 @@ def run_attend_case(kvr, rng, dtype, B, Hq, Hkv, r, w, ret_cap, n_vagues, vague_
             vague_pos[b, h, :n] = perm[ret_cap:ret_cap + n] if not identity else ret_cap + np.arange(n)
     out = torch.full((B, Hq, D), 9.0, dtype=torch.float32, device="cuda")
     sc = torch.as_tensor(scores0).cuda() if with_scores else None
-    ws = kvr.alloc_workspace(d, kvr.KVR_OP_ATTEND, ret_cap + vague_cap)
+    ws = kvr.alloc_workspace(d, kvr.KVR_OP_ATTEND, ret_cap, vague_cap)
     kvr.kvr_attend_decode(
         d, U.to_dev(q, dtype), U.to_dev(K, dtype), U.to_dev(V, dtype),
         None if identity else torch.as_tensor(ret_pos).cuda(), ret_cap,
@@ -384,6 +384,24 @@ def test_attend_edges(kvr, dtype):
     run_attend_case(kvr, rng, dtype, 1, 8, 2, 3, 6, 50, [-4, 9999], 120)
 
 
+def test_attend_staged_channel_chunks(kvr):
+    """bf16, r in {3, 4}, G <= 4 takes the LDS-staged kernel; the width of a
+    sketch row decides how many channels fit per phase (64 / 32 / 16 / 8).  Several
+    workgroups per unit, ragged last round, more than one 64-token round per wave."""
+    rng = np.random.default_rng(55)
+    dtype = torch.bfloat16
+    for (G, r, w, nv, cap, mode) in [(4, 3, 273, [5000, 4097], 5200, 0),      # 64 channels per phase
+                                     (4, 3, 400, [700, 1], 800, 0),           # 32
+                                     (2, 4, 500, [600, 333], 640, 0),         # 16, midmean
+                                     (2, 4, 500, [600, 333], 640, 1),         # 16, lower
+                                     (1, 3, 2000, [300, 64], 320, 0),         # 8
+                                     (4, 4, 30, [900, 65], 1000, 0)]:         # 64, r = 4
+        say("attend staged", G, r, w, nv, mode)
+        run_attend_case(kvr, rng, dtype, 1, 2 * G, 2, r, w, 130, nv, cap, mode=mode)
+    say("attend staged, many units (XCD mapping), 3 rounds per wave")
+    run_attend_case(kvr, rng, dtype, 3, 12, 3, 3, 50, 70, [4000, 3999, 1, 0, 64, 65, 2500, 4100, 128], 4100)
+
+
 def test_full_budget_matches_library_sdpa(kvr):
     """n_vague = 0 must be textbook softmax(qK^T/sqrt(d))V: checked against
     torch's SDPA on the CPU in float64 (not the oracle)."""
@@ -421,8 +439,9 @@ def test_fused_equals_dense_over_kvr_reconstruct(kvr):
     vp = (R + torch.arange(A, dtype=torch.int32, device="cuda")).expand(B, Hkv, A).contiguous()
     nv = torch.full((B, Hkv), A, dtype=torch.int32, device="cuda")
     out1 = torch.zeros(B, Hq, D, device="cuda")
-    ws = kvr.alloc_workspace(d, kvr.KVR_OP_ATTEND, R + A)
-    kvr.kvr_attend_decode(d, q, K, V, rp, R, SK, SV, vp, nv, A, out1, None, R + A, ws)
+    ws = kvr.alloc_workspace(d, kvr.KVR_OP_ATTEND, R + A, 0)
+    ws1 = kvr.alloc_workspace(d, kvr.KVR_OP_ATTEND, R, A)
+    kvr.kvr_attend_decode(d, q, K, V, rp, R, SK, SV, vp, nv, A, out1, None, R + A, ws1)
     kh, vh = torch.zeros(B, Hkv, A, D, dtype=dtype, device="cuda"), torch.zeros(B, Hkv, A, D, dtype=dtype, device="cuda")
     kvr.kvr_reconstruct(d, SK, SV, vp, nv, A, kh, vh)
     Kc, Vc = torch.cat([K, kh], dim=2).contiguous(), torch.cat([V, vh], dim=2).contiguous()
