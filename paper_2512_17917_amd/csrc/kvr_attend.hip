@@ -62,14 +62,26 @@ AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long
       p.staged = true;
       p.ch = ch;
       p.n_vslices = best_n;
-      p.lds_bytes = (int)align_up((size_t)d.r * d.w * ch * 2, 16) + fixed;
+      // the chunk buffer doubles as reduction scratch [32 rows][G][ch] floats
+      size_t buf = align_up((size_t)d.r * d.w * ch * 2, 16);
+      const size_t red = (size_t)32 * d.G * ch * 4;
+      if (buf < red) buf = red;
+      p.lds_bytes = (int)buf + fixed;
     }
   }
-  if (p.staged) {
+  p.mfma_retained = (dtype == KVR_BF16);
+  p.vslice_tokens = 0;
+  if (p.mfma_retained || p.staged) {
+    // retained slots and the Vague list are cut separately
     p.rslice_tokens = slice_tokens_for(ret_cap, units);
     p.n_rslices = (int)((ret_cap + p.rslice_tokens - 1) / p.rslice_tokens);
+    if (!p.staged && vague_cap > 0) {
+      p.vslice_tokens = slice_tokens_for(vague_cap, units);
+      p.n_vslices = (int)((vague_cap + p.vslice_tokens - 1) / p.vslice_tokens);
+    }
     p.n_slices = p.n_rslices + p.n_vslices;
   } else {
+    // one generic launch over all tokens
     p.rslice_tokens = slice_tokens_for(tot_cap, units);
     p.n_rslices = (int)((tot_cap + p.rslice_tokens - 1) / p.rslice_tokens);
     if (p.n_rslices < 1) p.n_rslices = 1;
@@ -110,7 +122,7 @@ __global__ __launch_bounds__(256) void attend_main_kernel(DevDesc d, AttendArgs 
   const int nv = a.n_vague ? clampi(a.n_vague[unit], 0, a.vague_cap) : 0;
   const int tot_cap = a.ret_cap + a.vague_cap;
   const int total = min(a.ret_cap + nv, a.tok_limit);
-  const int t_begin = slice * a.slice_tokens;
+  const int t_begin = a.tok_start + slice * a.slice_tokens;
   const int t_end = min(t_begin + a.slice_tokens, total);
 
   const T* kret = (const T*)a.k_ret + (size_t)unit * a.ret_cap * D;
@@ -215,8 +227,8 @@ __global__ __launch_bounds__(256) void attend_main_kernel(DevDesc d, AttendArgs 
     }
   }
   __syncthreads();
-  float* po = a.part_o + ((size_t)unit * a.n_slices + slice) * G * D;
-  float* pml = a.part_ml + ((size_t)unit * a.n_slices + slice) * G * 2;
+  float* po = a.part_o + ((size_t)unit * a.n_slices + a.slice0 + slice) * G * D;
+  float* pml = a.part_ml + ((size_t)unit * a.n_slices + a.slice0 + slice) * G * 2;
   for (int idx = threadIdx.x; idx < G * D; idx += 256) {
     const int g = idx / D, c = idx % D;
     float M = s_m[0][g];
@@ -339,16 +351,35 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
   const int units = d.B * d.Hkv;
   AttendArgs a = a0;
   a.n_slices = plan.n_slices;
-  a.slice_tokens = plan.rslice_tokens;
   a.n_rslices = plan.n_rslices;
   a.n_vslices = plan.n_vslices;
-  a.tok_limit = plan.staged ? a.ret_cap : a.ret_cap + a.vague_cap;
   if (ev_start) (void)hipEventRecord(ev_start, st);
-  dim3 grid(plan.n_rslices, units);
-  if (dtype == KVR_F32) launch_main_r<float, G>(d, a, grid, st);
-  else launch_main_r<bf16_t, G>(d, a, grid, st);
-  hipError_t e = hipGetLastError();
-  if (e == hipSuccess && plan.staged) e = launch_attend_vague_staged(d, a, plan, st);
+  hipError_t e = hipSuccess;
+  // 1. retained slots (or, for f32 storage without staging, everything at once)
+  a.slice_tokens = plan.rslice_tokens;
+  a.tok_start = 0;
+  a.slice0 = 0;
+  if (plan.mfma_retained) {
+    e = launch_attend_retained(d, a, plan.n_rslices, st);
+  } else {
+    a.tok_limit = plan.staged ? a.ret_cap : a.ret_cap + a.vague_cap;
+    dim3 grid(plan.n_rslices, units);
+    if (dtype == KVR_F32) launch_main_r<float, G>(d, a, grid, st);
+    else launch_main_r<bf16_t, G>(d, a, grid, st);
+    e = hipGetLastError();
+  }
+  // 2. the Vague list
+  if (e == hipSuccess && plan.staged) {
+    e = launch_attend_vague_staged(d, a, plan, st);
+  } else if (e == hipSuccess && plan.mfma_retained && plan.n_vslices > 0) {
+    a.slice_tokens = plan.vslice_tokens;
+    a.tok_start = a.ret_cap;
+    a.tok_limit = a.ret_cap + a.vague_cap;
+    a.slice0 = plan.n_rslices;
+    dim3 grid(plan.n_vslices, units);
+    launch_main_r<bf16_t, G>(d, a, grid, st);
+    e = hipGetLastError();
+  }
   if (ev_stop) (void)hipEventRecord(ev_stop, st);
   if (e != hipSuccess) return e;
   const long long tot_cap = (long long)a.ret_cap + a.vague_cap;

@@ -17,9 +17,11 @@
 //     each of its r rows starting at piece (lane mod CH/8), so that at any
 //     moment 8 neighbouring lanes read 8 different 16-byte bank groups; q is
 //     kept in registers in the same rotated order.  No cross-lane reduction.
-//   V phases: CH/8 lanes share one token (8 channels each) and accumulate
-//     p * v in registers across all of the wave's tokens; the token's weights
-//     come from their owner lane by a lane permute.
+//   V phases: CH/16 lanes share one token (two pieces = 16 channels each) and
+//     accumulate p * v in registers across all of the wave's tokens; the
+//     token's weights come from their owner lane by a lane permute.  Lanes of
+//     odd token groups take their two pieces in the opposite order, so that 8
+//     neighbouring lanes (two tokens) again cover 8 different bank groups.
 // Per-channel median of three on packed bf16: v_med3_f16 on the raw bit
 // patterns (both formats are sign-magnitude with the exponent above the
 // mantissa, so the order of finite values is the same; zeros of either sign
@@ -34,6 +36,20 @@ constexpr int ST_WAVES = 8;
 constexpr int ST_KMAX = 6;
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// Development aid, compiled out unless KVR_PHASE_TIMING is defined: thread 0 of
+// every workgroup stamps the cycle counter at phase boundaries.
+#ifdef KVR_PHASE_TIMING
+__device__ unsigned long long g_phase_t[8192 * 16];
+#define KVR_STAMP(i)                                                              \
+  do {                                                                            \
+    if (threadIdx.x == 0 && blockIdx.x < 8192) g_phase_t[blockIdx.x * 16 + (i)] = clock64(); \
+  } while (0)
+#else
+#define KVR_STAMP(i) \
+  do {               \
+  } while (0)
+#endif
 
 __device__ __forceinline__ uint32_t med3_bf16x2(uint32_t a, uint32_t b, uint32_t c) {
   uint32_t dst;
@@ -54,53 +70,116 @@ __device__ __forceinline__ uint32_t pack_bf16_exact(float lo, float hi) {
   return (__float_as_uint(hi) & 0xffff0000u) | (__float_as_uint(lo) >> 16);
 }
 
+template <int R>
+__device__ __forceinline__ uint32_t median_dword(const uint32_t (&x)[R], int mode) {
+  if constexpr (R == 3) {
+    return med3_bf16x2(x[0], x[1], x[2]);
+  } else {
+    float lo[R], hi[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) { lo[i] = bf_lo(x[i]); hi[i] = bf_hi(x[i]); }
+    return pack_bf16_exact(median_rows<R, bf16_t>(lo, R, mode), median_rows<R, bf16_t>(hi, R, mode));
+  }
+}
+
 // Median over R rows of a 16-byte piece (8 packed bf16 channels).
 template <int R>
 __device__ __forceinline__ uint4 median_piece(const uint4 (&row)[R], int mode) {
-  uint4 m;
-  if constexpr (R == 3) {
-    m.x = med3_bf16x2(row[0].x, row[1].x, row[2].x);
-    m.y = med3_bf16x2(row[0].y, row[1].y, row[2].y);
-    m.z = med3_bf16x2(row[0].z, row[1].z, row[2].z);
-    m.w = med3_bf16x2(row[0].w, row[1].w, row[2].w);
-  } else {
-    const uint32_t* rw[R];
+  uint32_t x[R], y[R], z[R], w_[R];
 #pragma unroll
-    for (int i = 0; i < R; ++i) rw[i] = reinterpret_cast<const uint32_t*>(&row[i]);
-    uint32_t o[4];
-#pragma unroll
-    for (int dw = 0; dw < 4; ++dw) {
-      float lo[R], hi[R];
-#pragma unroll
-      for (int i = 0; i < R; ++i) { lo[i] = bf_lo(rw[i][dw]); hi[i] = bf_hi(rw[i][dw]); }
-      o[dw] = pack_bf16_exact(median_rows<R, bf16_t>(lo, R, mode), median_rows<R, bf16_t>(hi, R, mode));
-    }
-    m = make_uint4(o[0], o[1], o[2], o[3]);
-  }
-  return m;
+  for (int i = 0; i < R; ++i) { x[i] = row[i].x; y[i] = row[i].y; z[i] = row[i].z; w_[i] = row[i].w; }
+  return make_uint4(median_dword<R>(x, mode), median_dword<R>(y, mode), median_dword<R>(z, mode),
+                    median_dword<R>(w_, mode));
 }
 
 __device__ __forceinline__ uint4 xor4(uint4 v, uint32_t mask) {
   return make_uint4(v.x ^ mask, v.y ^ mask, v.z ^ mask, v.w ^ mask);
 }
 
-// token info: 4 x 16 bits; bits 0..14 bucket, bit 15 sign (1 = negative)
-__device__ __forceinline__ int info_bucket(uint2 inf, int i) {
-  const uint32_t wd = (i < 2) ? inf.x : inf.y;
-  return (int)((wd >> ((i & 1) * 16)) & 0x7fffu);
+// Workgroup barrier for data exchanged through LDS only: waits for this wave's
+// LDS traffic, not for its outstanding global stores (which __syncthreads would).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
-__device__ __forceinline__ uint32_t info_neg(uint2 inf, int i) {
-  const uint32_t wd = (i < 2) ? inf.x : inf.y;
-  return (wd >> ((i & 1) * 16 + 15)) & 1u;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+// Sum over the lanes of a 16-lane row whose lane numbers are equal modulo LPT
+// (row rotations by LPT, 2 LPT, ..., 8); every lane ends up with its class's sum.
+template <int LPT>
+__device__ __forceinline__ float row_sum(float x) {
+  if constexpr (LPT <= 1) x = dpp_add<0x121>(x);
+  if constexpr (LPT <= 2) x = dpp_add<0x122>(x);
+  if constexpr (LPT <= 4) x = dpp_add<0x124>(x);
+  return dpp_add<0x128>(x);
+}
+
+// token info: 4 x 16 bits; bits 0..14 = LDS row index (i * w + h_i(J)), bit 15 = 1 iff g_i(J) = -1
+template <int I>
+__device__ __forceinline__ uint32_t info_row(uint2 inf) {
+  const uint32_t wd = (I < 2) ? inf.x : inf.y;
+  return (I & 1) ? __builtin_amdgcn_ubfe(wd, 16, 15) : (wd & 0x7fffu);
+}
+template <int I>
+__device__ __forceinline__ uint32_t info_neg(uint2 inf) {
+  const uint32_t wd = (I < 2) ? inf.x : inf.y;
+  return __builtin_amdgcn_ubfe(wd, (I & 1) * 16 + 15, 1);
+}
+// 0x80008000 if the signs of rows I and 0 differ, else 0
+template <int I>
+__device__ __forceinline__ uint32_t info_flipmask(uint2 inf) {
+  const uint32_t wd = (I < 2) ? inf.x : inf.y;
+  const uint32_t x = wd ^ (inf.x << ((I & 1) * 16));      // bit (I&1)*16+15 = sign_I ^ sign_0
+  return (uint32_t)__builtin_amdgcn_sbfe(x, (I & 1) * 16 + 15, 1) & 0x80008000u;
+}
+
+template <int R>
+__device__ __forceinline__ void row_offsets(uint2 inf, int (&rb)[R], int rowb_log2) {
+  rb[0] = (int)(info_row<0>(inf) << rowb_log2);
+  if constexpr (R > 1) rb[1] = (int)(info_row<1>(inf) << rowb_log2);
+  if constexpr (R > 2) rb[2] = (int)(info_row<2>(inf) << rowb_log2);
+  if constexpr (R > 3) rb[3] = (int)(info_row<3>(inf) << rowb_log2);
+}
+
+// Copy channel chunk `cc` of a sketch tensor [rows][128] (bf16, global) into LDS
+// rows of ROWB bytes.  Seven 16-byte loads per thread are put in flight before
+// the first one is stored.
+template <int NC, int ROWB>
+__device__ __forceinline__ void stage_chunk(const unsigned char* __restrict__ g, unsigned char* s_sk,
+                                            int n_pieces, int cc, int tid) {
+  constexpr int BATCH = 7;
+  for (int base = tid; base < n_pieces; base += ST_THREADS * BATCH) {
+    uint4 v[BATCH];
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      const int idx = min(base + u * ST_THREADS, n_pieces - 1);     // tail lanes re-read the last piece
+      const int row = idx / NC, c = idx % NC;
+      v[u] = *reinterpret_cast<const uint4*>(g + (size_t)row * (D * 2) + cc * ROWB + c * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      const int idx = base + u * ST_THREADS;
+      if (idx < n_pieces) {
+        const int row = idx / NC, c = idx % NC;
+        *reinterpret_cast<uint4*>(s_sk + row * ROWB + c * 16) = v[u];
+      }
+    }
+  }
 }
 
 template <int G, int R, int CH>
 __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc d, AttendArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int NC = CH / 8;          // 16-byte pieces per LDS row
-  constexpr int NPH = D / CH;         // phases per tensor
-  constexpr int ROWB = CH * 2;        // bytes per LDS row
-  constexpr int TPW = WAVE / NC;      // V phase: tokens per wave-iteration
+  constexpr int NC = CH / 8;                 // 16-byte pieces per LDS row
+  constexpr int NPH = D / CH;                // phases per tensor
+  constexpr int ROWB = CH * 2;               // bytes per LDS row
+  constexpr int ROWB_LOG2 = (CH == 64) ? 7 : (CH == 32) ? 6 : (CH == 16) ? 5 : 4;
+  constexpr int PPL = (NC >= 2) ? 2 : 1;     // V phase: pieces per lane
+  constexpr int LPT = NC / PPL;              // V phase: lanes per token
+  constexpr int TPW = WAVE / LPT;            // V phase: tokens per wave-iteration
+  constexpr int VCH = PPL * 8;               // V phase: channels per lane
 
   // XCD-aware mapping: workgroup ids are dealt round-robin to the 8 XCDs, so all
   // workgroups of a unit get ids that are equal modulo 8 (they share one L2).
@@ -114,11 +193,12 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = unit / d.Hkv, hk = unit % d.Hkv;
   const int w = d.w;
-  const int sk_bytes = (R * w * ROWB + 15) & ~15;
+  // chunk buffer; it doubles as reduction scratch [32 rows][G][CH] floats
+  const int sk_bytes = max((R * w * ROWB + 15) & ~15, 32 * G * CH * 4);
   unsigned char* s_sk = smem;
   uint2* s_info = reinterpret_cast<uint2*>(smem + sk_bytes);
   float* s_red = reinterpret_cast<float*>(smem + sk_bytes + ST_KMAX * ST_THREADS * 8);   // [8][G][CH]
-  float* s_stat = s_red + ST_WAVES * G * 64;                                               // [8][G] x 2, [G] x 2
+  float* s_stat = s_red + ST_WAVES * G * 64;                                               // [8][G] x 2
   uint4* s_q = reinterpret_cast<uint4*>(smem + sk_bytes + ST_KMAX * ST_THREADS * 8 + ST_WAVES * G * 64 * 4 + 1024);
 
   const int nv = clampi(a.n_vague[unit], 0, a.vague_cap);
@@ -128,7 +208,22 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   int n_k = gw < rounds_total ? (rounds_total - gw + NWT - 1) / NWT : 0;
   if (n_k > ST_KMAX) n_k = ST_KMAX;       // cannot happen when the plan was made for vague_cap
 
+  // ---- touch this workgroup's share of the unit's two sketches so that the
+  //      lines are on their way into L2 while the hashes are computed ----------
+  uint32_t touched = 0;
+  {
+    const int n_lines = 2 * R * w;                     // 128-byte lines per tensor
+    const int per_wg = (2 * n_lines + a.n_vslices - 1) / a.n_vslices;
+    const int li = vs * per_wg + tid;
+    if (tid < per_wg && li < 2 * n_lines) {
+      const bf16_t* base = (li < n_lines) ? (const bf16_t*)a.sk : (const bf16_t*)a.sv;
+      const int l2 = (li < n_lines) ? li : li - n_lines;
+      touched = *reinterpret_cast<const uint32_t*>(base + (size_t)unit * R * w * D + (size_t)l2 * 64);
+    }
+  }
+
   // ---- hash every token once; q to LDS ---------------------------------------
+  KVR_STAMP(0);
   uint2 info[ST_KMAX];
   uint32_t vmask = 0;
   const int32_t* vpos = a.vague_pos + (size_t)unit * a.vague_cap;
@@ -140,13 +235,15 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
       const int J = vpos[tok];
       uint32_t f[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-      for (int i = 0; i < R; ++i) f[i] = (uint32_t)bucket_of(d, i, J) | (sign_neg(d, i, J) ? 0x8000u : 0u);
+      for (int i = 0; i < R; ++i)
+        f[i] = (uint32_t)(i * w + bucket_of(d, i, J)) | (sign_neg(d, i, J) ? 0x8000u : 0u);
       pk = make_uint2(f[0] | (f[1] << 16), f[2] | (f[3] << 16));
       vmask |= 1u << k;
     }
     info[k] = pk;
     s_info[(k * ST_WAVES + wave) * 64 + lane] = pk;
   }
+  if (touched == 0x7fc1u && nv < 0) vmask = 0;       // never true; keeps the touch load alive
   if (tid < G * 16) {
     const uint4* qg = reinterpret_cast<const uint4*>((const bf16_t*)a.q + ((size_t)b * d.Hq + (size_t)hk * G) * D);
     s_q[tid] = qg[tid];
@@ -158,6 +255,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   const int n_pieces = R * w * NC;
 
   // ---- K phases: logits -----------------------------------------------------
+  KVR_STAMP(1);
   float s[ST_KMAX][G];
 #pragma unroll
   for (int k = 0; k < ST_KMAX; ++k)
@@ -165,13 +263,10 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
     for (int g = 0; g < G; ++g) s[k][g] = 0.f;
 
   for (int cc = 0; cc < NPH; ++cc) {
-    __syncthreads();
-    for (int idx = tid; idx < n_pieces; idx += ST_THREADS) {
-      const int row = idx / NC, c = idx % NC;
-      const uint4 v = *reinterpret_cast<const uint4*>(skg + (size_t)row * (D * 2) + cc * ROWB + c * 16);
-      *reinterpret_cast<uint4*>(s_sk + row * ROWB + c * 16) = v;
-    }
-    __syncthreads();
+    lds_barrier();
+    stage_chunk<NC, ROWB>(skg, s_sk, n_pieces, cc, tid);
+    lds_barrier();
+    KVR_STAMP(2 + 2 * cc);
     uint4 qreg[NC][G];
 #pragma unroll
     for (int j = 0; j < NC; ++j)
@@ -181,8 +276,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
     for (int k = 0; k < ST_KMAX; ++k) {
       if (k < n_k) {
         int rb[R];
-#pragma unroll
-        for (int i = 0; i < R; ++i) rb[i] = (i * w + info_bucket(info[k], i)) * ROWB;
+        row_offsets<R>(info[k], rb, ROWB_LOG2);
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
           const int co = ((lane + j) & (NC - 1)) * 16;
@@ -202,6 +296,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
         }
       }
     }
+    KVR_STAMP(3 + 2 * cc);
   }
 
   // ---- softmax weights against the workgroup's own maximum -------------------
@@ -234,31 +329,28 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
     for (int off = 1; off < WAVE; off <<= 1) mx[g] = fmaxf(mx[g], __shfl_xor(mx[g], off));
     if (lane == 0) s_stat[wave * G + g] = mx[g];
   }
-  __syncthreads();
-  float M[G], lsum[G];
+  lds_barrier();
+  float lsum[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    float v = s_stat[g];
+    float M = s_stat[g];
 #pragma unroll
-    for (int w_ = 1; w_ < ST_WAVES; ++w_) v = fmaxf(v, s_stat[w_ * G + g]);
-    M[g] = v;
+    for (int w_ = 1; w_ < ST_WAVES; ++w_) M = fmaxf(M, s_stat[w_ * G + g]);
     lsum[g] = 0.f;
-  }
 #pragma unroll
-  for (int k = 0; k < ST_KMAX; ++k)
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const float p = (s[k][g] == -__builtin_inff()) ? 0.f : expf(s[k][g] - M[g]);
+    for (int k = 0; k < ST_KMAX; ++k) {
+      const float p = (s[k][g] == -__builtin_inff()) ? 0.f : __expf(s[k][g] - M);
       s[k][g] = p;                 // from here on s holds the weights
       lsum[g] += p;
     }
+  }
 #pragma unroll
   for (int g = 0; g < G; ++g) {
 #pragma unroll
     for (int off = 1; off < WAVE; off <<= 1) lsum[g] += __shfl_xor(lsum[g], off);
     if (lane == 0) s_stat[ST_WAVES * G + wave * G + g] = lsum[g];
   }
-  __syncthreads();
+  lds_barrier();
   const size_t part = (size_t)unit * a.n_slices + a.n_rslices + vs;
   if (tid < G) {
     float L = 0.f, Mg = s_stat[tid];
@@ -272,78 +364,118 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   }
 
   // ---- V phases: weighted values ------------------------------------------------
-  const int sub = lane % NC, tl = lane / NC;
+  KVR_STAMP(6);
+  const int sub = lane % LPT, tl = lane / LPT;
+  // the two pieces of this lane: odd token groups take them in the opposite order
+  const int pa = (PPL == 2) ? sub + ((tl & 1) ? LPT : 0) : sub;
+  const int pb = (PPL == 2) ? sub + ((tl & 1) ? 0 : LPT) : sub;
   for (int cc = 0; cc < NPH; ++cc) {
-    __syncthreads();
-    for (int idx = tid; idx < n_pieces; idx += ST_THREADS) {
-      const int row = idx / NC, c = idx % NC;
-      const uint4 v = *reinterpret_cast<const uint4*>(svg + (size_t)row * (D * 2) + cc * ROWB + c * 16);
-      *reinterpret_cast<uint4*>(s_sk + row * ROWB + c * 16) = v;
-    }
-    __syncthreads();
-    float acc[G][8];
+    lds_barrier();
+    stage_chunk<NC, ROWB>(svg, s_sk, n_pieces, cc, tid);
+    lds_barrier();
+    KVR_STAMP(7 + 2 * cc);
+    float acc[G][VCH];
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int c = 0; c < 8; ++c) acc[g][c] = 0.f;
+      for (int c = 0; c < VCH; ++c) acc[g][c] = 0.f;
 #pragma unroll
     for (int k = 0; k < ST_KMAX; ++k) {
       if (k < n_k) {
-        for (int j8 = 0; j8 < NC; ++j8) {
+#pragma unroll
+        for (int j8 = 0; j8 < LPT; ++j8) {
           const int owner = j8 * TPW + tl;
           const uint2 inf = s_info[(k * ST_WAVES + wave) * 64 + owner];
           float pg[G];
 #pragma unroll
           for (int g = 0; g < G; ++g) pg[g] = __shfl(s[k][g], owner);
-          uint4 row[R];
-#pragma unroll
-          for (int i = 0; i < R; ++i)
-            row[i] = *reinterpret_cast<const uint4*>(s_sk + (i * w + info_bucket(inf, i)) * ROWB + sub * 16);
+          int rb[R];
+          row_offsets<R>(inf, rb, ROWB_LOG2);
+          uint32_t fm[R];
           if constexpr (R == 3) {
             // g_0 goes onto the weight; rows 1, 2 are flipped relative to row 0
-            const uint32_t n0 = info_neg(inf, 0);
-            row[1] = xor4(row[1], (info_neg(inf, 1) ^ n0) ? 0x80008000u : 0u);
-            row[2] = xor4(row[2], (info_neg(inf, 2) ^ n0) ? 0x80008000u : 0u);
-            const uint32_t sgn = n0 << 31;
+            fm[0] = 0u;
+            fm[1] = info_flipmask<1>(inf);
+            fm[2] = info_flipmask<2>(inf);
+            const uint32_t sgn = inf.x << 16 & 0x80000000u;
 #pragma unroll
             for (int g = 0; g < G; ++g) pg[g] = __uint_as_float(__float_as_uint(pg[g]) ^ sgn);
           } else {
-#pragma unroll
-            for (int i = 0; i < R; ++i) row[i] = xor4(row[i], info_neg(inf, i) ? 0x80008000u : 0u);
+            fm[0] = info_neg<0>(inf) ? 0x80008000u : 0u;
+            fm[1] = info_neg<1>(inf) ? 0x80008000u : 0u;
+            fm[2] = info_neg<2>(inf) ? 0x80008000u : 0u;
+            if constexpr (R > 3) fm[3] = info_neg<3>(inf) ? 0x80008000u : 0u;
           }
-          const uint4 m = median_piece<R>(row, d.median_mode);
-          const float v[8] = {bf_lo(m.x), bf_hi(m.x), bf_lo(m.y), bf_hi(m.y),
-                              bf_lo(m.z), bf_hi(m.z), bf_lo(m.w), bf_hi(m.w)};
 #pragma unroll
-          for (int g = 0; g < G; ++g)
+          for (int h = 0; h < PPL; ++h) {
+            const int co = (h == 0 ? pa : pb) * 16;
+            uint4 row[R];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) acc[g][c] = fmaf(pg[g], v[c], acc[g][c]);
+            for (int i = 0; i < R; ++i) {
+              row[i] = *reinterpret_cast<const uint4*>(s_sk + rb[i] + co);
+              if (!(R == 3 && i == 0)) row[i] = xor4(row[i], fm[i]);
+            }
+            const uint4 m = median_piece<R>(row, d.median_mode);
+            const float v[8] = {bf_lo(m.x), bf_hi(m.x), bf_lo(m.y), bf_hi(m.y),
+                                bf_lo(m.z), bf_hi(m.z), bf_lo(m.w), bf_hi(m.w)};
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+              for (int c = 0; c < 8; ++c) acc[g][h * 8 + c] = fmaf(pg[g], v[c], acc[g][h * 8 + c]);
+          }
         }
       }
     }
-    // lanes with equal `sub` hold the same channels: add them up, then the waves
-#pragma unroll
-    for (int off = NC; off < WAVE; off <<= 1)
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[g][c] += __shfl_xor(acc[g][c], off);
-    if (tl == 0) {
+    KVR_STAMP(8 + 2 * cc);
+    // odd token groups hold their two pieces swapped: put them in piece order
+    if constexpr (PPL == 2) {
+      const bool odd = (tl & 1) != 0;
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) s_red[(wave * G + g) * CH + sub * 8 + c] = acc[g][c];
+        for (int c = 0; c < 8; ++c) {
+          const float lo = acc[g][c], hi = acc[g][8 + c];
+          acc[g][c] = odd ? hi : lo;
+          acc[g][8 + c] = odd ? lo : hi;
+        }
     }
-    __syncthreads();
+    // lanes with equal `sub` hold the same channels.  Inside a row of 16 lanes
+    // they are added with DPP rotations (no LDS traffic); the 4 rows of the 8
+    // waves then meet in LDS, in the space of the sketch chunk, which nobody
+    // reads any more after the barrier.
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int c = 0; c < VCH; ++c) acc[g][c] = row_sum<LPT>(acc[g][c]);
+    lds_barrier();
+    float* s_part = reinterpret_cast<float*>(s_sk);          // [8 waves * 4 rows][G][CH]
+    if ((lane & 15) < LPT) {
+      const int prow = wave * 4 + (lane >> 4);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int h = 0; h < PPL; ++h) {
+          float* dst = s_part + (prow * G + g) * CH + (sub + h * LPT) * 8;
+          *reinterpret_cast<float4*>(dst) = make_float4(acc[g][h * 8], acc[g][h * 8 + 1], acc[g][h * 8 + 2], acc[g][h * 8 + 3]);
+          *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[g][h * 8 + 4], acc[g][h * 8 + 5], acc[g][h * 8 + 6], acc[g][h * 8 + 7]);
+        }
+    }
+    lds_barrier();
     for (int idx = tid; idx < G * CH; idx += ST_THREADS) {
-      const int g = idx / CH, c = idx % CH;
       float o = 0.f;
 #pragma unroll
-      for (int w_ = 0; w_ < ST_WAVES; ++w_) o += s_red[(w_ * G + g) * CH + c];
-      a.part_o[(part * G + g) * D + cc * CH + c] = o;
+      for (int pr = 0; pr < ST_WAVES * 4; ++pr) o += s_part[pr * G * CH + idx];
+      a.part_o[part * G * D + (idx / CH) * D + cc * CH + (idx % CH)] = o;
     }
   }
+  KVR_STAMP(11);
 }
+
+#ifdef KVR_PHASE_TIMING
+extern "C" int kvr_debug_phase_times(unsigned long long* host_out, int n_words) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_phase_t), (size_t)n_words * 8, 0, hipMemcpyDeviceToHost);
+}
+#endif
 
 template <int G, int R, int CH>
 static hipError_t launch_one(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {

@@ -11,11 +11,13 @@ namespace kvr {
 // How one kvr_attend_decode call is cut into workgroups.  Slices 0 .. n_rslices-1
 // cover the retained slots, slices n_rslices .. n_slices-1 the Vague index list.
 struct AttendPlan {
-  bool staged;          // Vague tokens by the LDS-staged kernel (else the generic kernel does everything)
+  bool staged;          // Vague tokens by the LDS-staged kernel (else by the generic kernel)
+  bool mfma_retained;   // retained slots by the MFMA kernel (bf16) (else by the generic kernel)
   int n_slices;         // partial results per unit
   int n_rslices;        // of which: retained slices
-  int rslice_tokens;    // tokens per retained (or, generic path, any) slice
-  int n_vslices;        // staged: workgroups per unit over the Vague list
+  int rslice_tokens;    // tokens per retained slice
+  int n_vslices;        // slices (generic) or workgroups (staged) per unit over the Vague list
+  int vslice_tokens;    // generic kernel over the Vague list: tokens per slice
   int ch;               // staged: channels per LDS phase
   int lds_bytes;        // staged: dynamic LDS per workgroup
   size_t off_part_o, off_part_ml, off_logits, total_bytes;
@@ -41,11 +43,16 @@ struct AttendArgs {
   float* part_ml;    // [units, n_slices, G, 2]
   float* logits;     // [units, ret_cap + vague_cap, G] or nullptr when scores == nullptr
   int n_slices;      // partial results per unit (all kinds)
-  int slice_tokens;  // generic kernel: tokens per slice
+  int slice_tokens;  // generic / retained kernel: tokens per slice
+  int tok_start;     // generic kernel: first token it handles
   int tok_limit;     // generic kernel: it handles tokens t < min(tok_limit, ret_cap + n_vague)
+  int slice0;        // generic kernel: index of its first partial
   int n_rslices;     // staged kernel: index of its first partial
   int n_vslices;     // staged kernel: workgroups per unit
 };
+
+// Retained slots by the MFMA kernel (bf16): slices 0 .. n_rslices-1 of a.slice_tokens slots.
+hipError_t launch_attend_retained(const DevDesc& d, const AttendArgs& a, int n_rslices, hipStream_t st);
 
 struct EncodePlan {
   bool bulk;
