@@ -13,6 +13,8 @@
 // sign setting; Vague rows gathered straight from global memory), the merge
 // kernel and the dispatch.  The LDS-staged kernel for the Vague list is in
 // kvr_attend_staged.hip.
+#include <stdlib.h>
+
 #include "kvr_launch.h"
 
 namespace kvr {
@@ -44,7 +46,7 @@ AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long
     const int fixed = STAGED_KMAX * 512 * 8 + 8 * d.G * 64 * 4 + 1024 + d.G * 256;
     int ch = 0;
     for (int c = 64; c >= 8; c >>= 1) {
-      if ((long long)d.r * d.w * c * 2 + fixed + 64 <= STAGED_LDS_LIMIT) { ch = c; break; }
+      if ((long long)d.r * d.w * c * 2 + 1024 + fixed <= STAGED_LDS_LIMIT) { ch = c; break; }
     }
     if (ch) {
       const long long wr = (vague_cap + 63) / 64;          // wave-rounds to cover the list
@@ -63,7 +65,8 @@ AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long
       p.ch = ch;
       p.n_vslices = best_n;
       // the chunk buffer doubles as reduction scratch [32 rows][G][ch] floats
-      size_t buf = align_up((size_t)d.r * d.w * ch * 2, 16);
+      // and is padded to whole kilobytes (a wave stages 1 KB at a time)
+      size_t buf = align_up((size_t)d.r * d.w * ch * 2, 1024);
       const size_t red = (size_t)32 * d.G * ch * 4;
       if (buf < red) buf = red;
       p.lds_bytes = (int)buf + fixed;
@@ -336,6 +339,49 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
 }
 
 // ---------------------------------------------------------------------------
+// Side stream for running the retained kernel next to the staged kernel.  One
+// per host thread, created on first use (default priority, non-blocking), kept
+// until the process ends.  KVR_NO_OVERLAP=1 in the environment switches the
+// overlap off (both kernels then run back to back on the caller's stream).
+struct SideStream {
+  hipStream_t stream;
+  hipEvent_t fork, join;
+};
+
+static bool overlap_enabled() {
+  static const bool on = []() {
+    const char* v = getenv("KVR_NO_OVERLAP");
+    return !(v != nullptr && v[0] == '1');
+  }();
+  return on;
+}
+
+static int cu_count() {
+  static const int n = []() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+      cus = 256;
+    return cus;
+  }();
+  return n;
+}
+
+static SideStream* side_stream() {
+  thread_local SideStream s = {nullptr, nullptr, nullptr};
+  thread_local int state = 0;        // 0 = not tried, 1 = ready, -1 = failed
+  if (state == 0) {
+    state = -1;
+    if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
+        hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
+        hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess)
+      state = 1;
+    else
+      (void)hipGetLastError();
+  }
+  return state == 1 ? &s : nullptr;
+}
+
 template <typename T, int G>
 static void launch_main_r(const DevDesc& d, const AttendArgs& a, dim3 grid, hipStream_t st) {
   switch (d.r) {
@@ -359,8 +405,19 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
   a.slice_tokens = plan.rslice_tokens;
   a.tok_start = 0;
   a.slice0 = 0;
-  if (plan.mfma_retained) {
-    e = launch_attend_retained(d, a, plan.n_rslices, st);
+  // The retained kernel is bound by HBM, the staged kernel by the vector ALUs and
+  // LDS, and their registers and LDS fit on a CU together: run them side by side,
+  // the retained kernel on a side stream forked from and joined back into `st`.
+  SideStream* side = (plan.mfma_retained && plan.staged && overlap_enabled()) ? side_stream() : nullptr;
+  if (side != nullptr) {
+    e = hipEventRecord(side->fork, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
+    if (e == hipSuccess) e = launch_attend_retained(d, a, plan.n_rslices, cu_count(), side->stream);
+    if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
+    if (e == hipSuccess) e = launch_attend_vague_staged(d, a, plan, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(st, side->join, 0);
+  } else if (plan.mfma_retained) {
+    e = launch_attend_retained(d, a, plan.n_rslices, 0, st);
   } else {
     a.tok_limit = plan.staged ? a.ret_cap : a.ret_cap + a.vague_cap;
     dim3 grid(plan.n_rslices, units);
@@ -369,7 +426,9 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
     e = hipGetLastError();
   }
   // 2. the Vague list
-  if (e == hipSuccess && plan.staged) {
+  if (side != nullptr) {
+    // already launched above
+  } else if (e == hipSuccess && plan.staged) {
     e = launch_attend_vague_staged(d, a, plan, st);
   } else if (e == hipSuccess && plan.mfma_retained && plan.n_vslices > 0) {
     a.slice_tokens = plan.vslice_tokens;

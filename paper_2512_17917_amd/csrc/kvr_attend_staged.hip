@@ -116,6 +116,18 @@ __device__ __forceinline__ float row_sum(float x) {
   return dpp_add<0x128>(x);
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float x) {
+  return fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false)));
+}
+// maximum over the 16 lanes of a row, in every lane
+__device__ __forceinline__ float row_max(float x) {
+  x = dpp_max<0x121>(x);
+  x = dpp_max<0x122>(x);
+  x = dpp_max<0x124>(x);
+  return dpp_max<0x128>(x);
+}
+
 // token info: 4 x 16 bits; bits 0..14 = LDS row index (i * w + h_i(J)), bit 15 = 1 iff g_i(J) = -1
 template <int I>
 __device__ __forceinline__ uint32_t info_row(uint2 inf) {
@@ -144,29 +156,25 @@ __device__ __forceinline__ void row_offsets(uint2 inf, int (&rb)[R], int rowb_lo
 }
 
 // Copy channel chunk `cc` of a sketch tensor [rows][128] (bf16, global) into LDS
-// rows of ROWB bytes.  Seven 16-byte loads per thread are put in flight before
-// the first one is stored.
+// rows of ROWB bytes with global->LDS loads that bypass the registers
+// (global_load_lds_dwordx4: lane i's 16 bytes land at the wave's LDS base +
+// 16 i).  Piece p of the chunk lives at LDS offset 16 p, so a wave that takes 64
+// consecutive pieces fills 1 KB of consecutive LDS.  All copies of a wave are
+// in flight together; the caller's barrier must follow the vmcnt wait done here.
+// Tail lanes re-read the last piece into the padding behind the chunk (the
+// buffer is sized to a multiple of 1 KB).
 template <int NC, int ROWB>
 __device__ __forceinline__ void stage_chunk(const unsigned char* __restrict__ g, unsigned char* s_sk,
                                             int n_pieces, int cc, int tid) {
-  constexpr int BATCH = 7;
-  for (int base = tid; base < n_pieces; base += ST_THREADS * BATCH) {
-    uint4 v[BATCH];
-#pragma unroll
-    for (int u = 0; u < BATCH; ++u) {
-      const int idx = min(base + u * ST_THREADS, n_pieces - 1);     // tail lanes re-read the last piece
-      const int row = idx / NC, c = idx % NC;
-      v[u] = *reinterpret_cast<const uint4*>(g + (size_t)row * (D * 2) + cc * ROWB + c * 16);
-    }
-#pragma unroll
-    for (int u = 0; u < BATCH; ++u) {
-      const int idx = base + u * ST_THREADS;
-      if (idx < n_pieces) {
-        const int row = idx / NC, c = idx % NC;
-        *reinterpret_cast<uint4*>(s_sk + row * ROWB + c * 16) = v[u];
-      }
-    }
+  const int lane = tid & 63, wave = tid >> 6;
+  for (int p0 = wave * 64; p0 < n_pieces; p0 += ST_THREADS) {
+    const int idx = min(p0 + lane, n_pieces - 1);
+    const int row = idx / NC, c = idx % NC;
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(g + (size_t)row * (D * 2) + cc * ROWB + c * 16),
+        (__attribute__((address_space(3))) void*)(s_sk + p0 * 16), 16, 0, 0);
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <int G, int R, int CH>
@@ -194,7 +202,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   const int b = unit / d.Hkv, hk = unit % d.Hkv;
   const int w = d.w;
   // chunk buffer; it doubles as reduction scratch [32 rows][G][CH] floats
-  const int sk_bytes = max((R * w * ROWB + 15) & ~15, 32 * G * CH * 4);
+  const int sk_bytes = max((R * w * ROWB + 1023) & ~1023, 32 * G * CH * 4);
   unsigned char* s_sk = smem;
   uint2* s_info = reinterpret_cast<uint2*>(smem + sk_bytes);
   float* s_red = reinterpret_cast<float*>(smem + sk_bytes + ST_KMAX * ST_THREADS * 8);   // [8][G][CH]
@@ -267,31 +275,37 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
     stage_chunk<NC, ROWB>(skg, s_sk, n_pieces, cc, tid);
     lds_barrier();
     KVR_STAMP(2 + 2 * cc);
-    uint4 qreg[NC][G];
+    // the pieces of a row are taken in two halves so that only half of q (in
+    // this lane's rotated order) has to sit in registers at a time
+    constexpr int JH = (NC >= 8) ? NC / 2 : NC;
 #pragma unroll
-    for (int j = 0; j < NC; ++j)
+    for (int j0 = 0; j0 < NC; j0 += JH) {
+      uint4 qreg[JH][G];
 #pragma unroll
-      for (int g = 0; g < G; ++g) qreg[j][g] = s_q[g * 16 + cc * NC + ((lane + j) & (NC - 1))];
+      for (int j = 0; j < JH; ++j)
 #pragma unroll
-    for (int k = 0; k < ST_KMAX; ++k) {
-      if (k < n_k) {
-        int rb[R];
-        row_offsets<R>(info[k], rb, ROWB_LOG2);
+        for (int g = 0; g < G; ++g) qreg[j][g] = s_q[g * 16 + cc * NC + ((lane + j0 + j) & (NC - 1))];
 #pragma unroll
-        for (int j = 0; j < NC; ++j) {
-          const int co = ((lane + j) & (NC - 1)) * 16;
-          uint4 row[R];
+      for (int k = 0; k < ST_KMAX; ++k) {
+        if (k < n_k) {
+          int rb[R];
+          row_offsets<R>(info[k], rb, ROWB_LOG2);
 #pragma unroll
-          for (int i = 0; i < R; ++i) row[i] = *reinterpret_cast<const uint4*>(s_sk + rb[i] + co);
-          const uint4 m = median_piece<R>(row, d.median_mode);
+          for (int j = 0; j < JH; ++j) {
+            const int co = ((lane + j0 + j) & (NC - 1)) * 16;
+            uint4 row[R];
 #pragma unroll
-          for (int g = 0; g < G; ++g) {
-            float x = s[k][g];
-            x = dot2_bf16(m.x, qreg[j][g].x, x);
-            x = dot2_bf16(m.y, qreg[j][g].y, x);
-            x = dot2_bf16(m.z, qreg[j][g].z, x);
-            x = dot2_bf16(m.w, qreg[j][g].w, x);
-            s[k][g] = x;
+            for (int i = 0; i < R; ++i) row[i] = *reinterpret_cast<const uint4*>(s_sk + rb[i] + co);
+            const uint4 m = median_piece<R>(row, d.median_mode);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+              float x = s[k][g];
+              x = dot2_bf16(m.x, qreg[j][g].x, x);
+              x = dot2_bf16(m.y, qreg[j][g].y, x);
+              x = dot2_bf16(m.z, qreg[j][g].z, x);
+              x = dot2_bf16(m.w, qreg[j][g].w, x);
+              s[k][g] = x;
+            }
           }
         }
       }
@@ -323,11 +337,14 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
       }
     }
   }
+  // maxima and sums: DPP inside each 16-lane row, then the 32 rows of the
+  // workgroup meet in LDS (s_stat: [32][G] maxima, [32][G] sums)
+  constexpr int NROW = ST_WAVES * 4;
+  const int prow = wave * 4 + (lane >> 4);
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-#pragma unroll
-    for (int off = 1; off < WAVE; off <<= 1) mx[g] = fmaxf(mx[g], __shfl_xor(mx[g], off));
-    if (lane == 0) s_stat[wave * G + g] = mx[g];
+    mx[g] = row_max(mx[g]);
+    if ((lane & 15) == 0) s_stat[prow * G + g] = mx[g];
   }
   lds_barrier();
   float lsum[G];
@@ -335,7 +352,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   for (int g = 0; g < G; ++g) {
     float M = s_stat[g];
 #pragma unroll
-    for (int w_ = 1; w_ < ST_WAVES; ++w_) M = fmaxf(M, s_stat[w_ * G + g]);
+    for (int pr = 1; pr < NROW; ++pr) M = fmaxf(M, s_stat[pr * G + g]);
     lsum[g] = 0.f;
 #pragma unroll
     for (int k = 0; k < ST_KMAX; ++k) {
@@ -346,18 +363,17 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   }
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-#pragma unroll
-    for (int off = 1; off < WAVE; off <<= 1) lsum[g] += __shfl_xor(lsum[g], off);
-    if (lane == 0) s_stat[ST_WAVES * G + wave * G + g] = lsum[g];
+    lsum[g] = row_sum<1>(lsum[g]);
+    if ((lane & 15) == 0) s_stat[NROW * G + prow * G + g] = lsum[g];
   }
   lds_barrier();
   const size_t part = (size_t)unit * a.n_slices + a.n_rslices + vs;
   if (tid < G) {
     float L = 0.f, Mg = s_stat[tid];
 #pragma unroll
-    for (int w_ = 0; w_ < ST_WAVES; ++w_) {
-      L += s_stat[ST_WAVES * G + w_ * G + tid];
-      Mg = fmaxf(Mg, s_stat[w_ * G + tid]);
+    for (int pr = 0; pr < NROW; ++pr) {
+      L += s_stat[NROW * G + pr * G + tid];
+      Mg = fmaxf(Mg, s_stat[pr * G + tid]);
     }
     a.part_ml[(part * G + tid) * 2] = Mg;
     a.part_ml[(part * G + tid) * 2 + 1] = L;

@@ -52,7 +52,9 @@ struct AttendArgs {
 };
 
 // Retained slots by the MFMA kernel (bf16): slices 0 .. n_rslices-1 of a.slice_tokens slots.
-hipError_t launch_attend_retained(const DevDesc& d, const AttendArgs& a, int n_rslices, hipStream_t st);
+// max_wgs > 0 caps the launch width (the workgroups then walk the items with a grid stride).
+hipError_t launch_attend_retained(const DevDesc& d, const AttendArgs& a, int n_rslices, int max_wgs,
+                                  hipStream_t st);
 
 struct EncodePlan {
   bool bulk;
