@@ -202,6 +202,21 @@ int32_t kvr_encode(const kvr_desc* desc, const void* k_src, const void* v_src, i
                    void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Algorithm 3 for one decode step, in one launch: exactly kvr_append, then
+ * kvr_select, then kvr_encode of the tokens that kvr_select listed (read from
+ * the retained slots they just left), with the same arguments, the same results
+ * and the same bit-reproducible sketch as the three separate calls.  For the
+ * decode steady state only: ret_cap <= 8192 and evict_cap <= 64, otherwise
+ * KVR_ERR_UNSUPPORTED (compress a prompt with the separate calls).
+ */
+int32_t kvr_step_update(const kvr_desc* desc, const void* k_new, const void* v_new, const int32_t* n_ctx,
+                        void* k_ret, void* v_ret, int32_t* ret_pos, int32_t ret_cap,
+                        const float* scores, int64_t n_cap, int32_t n_recent, int32_t k_candidate,
+                        int32_t* evict_slot, int32_t* evict_pos, int32_t* n_evict, int32_t evict_cap,
+                        int32_t* vague_pos, int32_t* n_vague, int32_t vague_cap,
+                        void* sketch_k, void* sketch_v, void* stream);
+
+/*
  * Algorithm 2, batched: for token position J = tok_pos[u, e], e < count[u],
  *     k_out[u, e, c] = median_i sketch_k[u, i, h_i(J), c]
  *     v_out[u, e, c] = median_i g_i(J) * sketch_v[u, i, h_i(J), c]

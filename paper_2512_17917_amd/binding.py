@@ -30,8 +30,8 @@ _ERR_NAMES = {-1: "KVR_ERR_INVALID_ARG", -2: "KVR_ERR_UNSUPPORTED",
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvr.so")
 
 EXPORTS = ["kvr_version", "kvr_last_hip_error", "kvr_profile_events", "kvr_hash_params_from_seed", "kvr_hash_host",
-           "kvr_workspace_size", "kvr_append", "kvr_select", "kvr_encode", "kvr_reconstruct",
-           "kvr_attend_decode"]
+           "kvr_workspace_size", "kvr_append", "kvr_select", "kvr_encode", "kvr_step_update",
+           "kvr_reconstruct", "kvr_attend_decode"]
 
 
 class KvrError(RuntimeError):
@@ -80,6 +80,9 @@ def lib() -> C.CDLL:
                                  vp, sz, vp]
         L.kvr_encode.restype = i32
         L.kvr_encode.argtypes = [dp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.kvr_step_update.restype = i32
+        L.kvr_step_update.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, i64, i32, i32, vp, vp, vp, i32,
+                                      vp, vp, i32, vp, vp, vp]
         L.kvr_reconstruct.restype = i32
         L.kvr_reconstruct.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp]
         L.kvr_attend_decode.restype = i32
@@ -229,6 +232,26 @@ def kvr_encode(desc, k_src, v_src, src_rows, src_slot, tok_pos, count, cap, sket
         _ptr(out_bucket, torch.int32, U * cap * desc.r, "out_bucket", True),
         _ptr(out_sign, torch.uint8, U * cap, "out_sign", True), wp, wb, _stream())
     _check("kvr_encode", rc)
+
+
+def kvr_step_update(desc, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap, scores, n_cap, n_recent,
+                    k_candidate, evict_slot, evict_pos, n_evict, evict_cap, vague_pos, n_vague, vague_cap,
+                    sketch_k, sketch_v):
+    U, D, dt = desc.batch * desc.n_kv_heads, desc.head_dim, _torch_dtype(desc)
+    S = desc.r * desc.w * D
+    rc = lib().kvr_step_update(
+        C.byref(desc), _ptr(k_new, dt, U * D, "k_new"), _ptr(v_new, dt, U * D, "v_new"),
+        _ptr(n_ctx, torch.int32, desc.batch, "n_ctx"),
+        _ptr(k_ret, dt, U * ret_cap * D, "k_ret"), _ptr(v_ret, dt, U * ret_cap * D, "v_ret"),
+        _ptr(ret_pos, torch.int32, U * ret_cap, "ret_pos"), ret_cap,
+        _ptr(scores, torch.float32, U * n_cap, "scores"), n_cap, n_recent, k_candidate,
+        _ptr(evict_slot, torch.int32, U * evict_cap, "evict_slot"),
+        _ptr(evict_pos, torch.int32, U * evict_cap, "evict_pos"),
+        _ptr(n_evict, torch.int32, U, "n_evict"), evict_cap,
+        _ptr(vague_pos, torch.int32, U * vague_cap, "vague_pos", True),
+        _ptr(n_vague, torch.int32, U, "n_vague", True), vague_cap,
+        _ptr(sketch_k, dt, U * S, "sketch_k"), _ptr(sketch_v, dt, U * S, "sketch_v"), _stream())
+    _check("kvr_step_update", rc)
 
 
 def kvr_reconstruct(desc, sketch_k, sketch_v, tok_pos, count, cap, k_out, v_out):

@@ -168,6 +168,31 @@ int32_t kvr_encode(const kvr_desc* desc, const void* k_src, const void* v_src, i
                                    sketch_k, sketch_v, out_bucket, out_sign, ws, plan, (hipStream_t)stream));
 }
 
+int32_t kvr_step_update(const kvr_desc* desc, const void* k_new, const void* v_new, const int32_t* n_ctx,
+                        void* k_ret, void* v_ret, int32_t* ret_pos, int32_t ret_cap, const float* scores,
+                        int64_t n_cap, int32_t n_recent, int32_t k_candidate, int32_t* evict_slot,
+                        int32_t* evict_pos, int32_t* n_evict, int32_t evict_cap, int32_t* vague_pos,
+                        int32_t* n_vague, int32_t vague_cap, void* sketch_k, void* sketch_v, void* stream) {
+  kvr::DevDesc d;
+  const int32_t rc = check_desc(desc, d);
+  if (rc != KVR_OK) return rc;
+  if (!k_new || !v_new || !n_ctx || !k_ret || !v_ret || !ret_pos || !scores || !evict_slot || !evict_pos ||
+      !n_evict || !sketch_k || !sketch_v)
+    return KVR_ERR_INVALID_ARG;
+  if ((vague_pos == nullptr) != (n_vague == nullptr)) return KVR_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_ret) || !aligned16(v_ret) ||
+      !aligned16(sketch_k) || !aligned16(sketch_v))
+    return KVR_ERR_INVALID_ARG;
+  if (n_cap < 1 || n_cap > MAX_TOKENS || ret_cap < 1 || n_recent < 0 || k_candidate < 0 || evict_cap < 1)
+    return KVR_ERR_INVALID_ARG;
+  if (vague_pos != nullptr && vague_cap < 1) return KVR_ERR_INVALID_ARG;
+  if (ret_cap > 8192 || evict_cap > 64) return KVR_ERR_UNSUPPORTED;
+  return finish(kvr::launch_step_update(d, desc->dtype, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap,
+                                        scores, n_cap, n_recent, k_candidate, evict_slot, evict_pos, n_evict,
+                                        evict_cap, vague_pos, n_vague, vague_cap, sketch_k, sketch_v,
+                                        (hipStream_t)stream));
+}
+
 int32_t kvr_reconstruct(const kvr_desc* desc, const void* sketch_k, const void* sketch_v,
                         const int32_t* tok_pos, const int32_t* count, int32_t cap, void* k_out, void* v_out,
                         void* stream) {

@@ -13,10 +13,10 @@
 //     inside a slot), then one wave per (unit, row, slot) adds its segment
 //     sequentially, lanes across channels.
 #include "kvr_launch.h"
+#include "kvr_update.h"
 
 namespace kvr {
 
-constexpr int ENC_SMALL_CAP = 64;
 constexpr int ENC_BULK_MAX_W = 8192;     // LDS cursor array of the sort kernel
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -42,56 +42,13 @@ EncodePlan encode_plan(const DevDesc& d, long long cap) {
 
 // ------------------------------------------------------------------ small
 template <typename T>
-__global__ __launch_bounds__(D) void encode_small_kernel(
+__global__ __launch_bounds__(4 * D) void encode_small_kernel(
     DevDesc d, const T* __restrict__ k_src, const T* __restrict__ v_src, int src_rows,
     const int32_t* __restrict__ src_slot, const int32_t* __restrict__ tok_pos,
     const int32_t* __restrict__ count, int cap, T* __restrict__ sk, T* __restrict__ sv,
     int32_t* __restrict__ out_bucket, uint8_t* __restrict__ out_sign) {
-  __shared__ int s_bucket[ENC_SMALL_CAP][KVR_MAX_ROWS];
-  __shared__ int s_slot[ENC_SMALL_CAP];
-  __shared__ unsigned s_sign[ENC_SMALL_CAP];
-  const int unit = blockIdx.x;
-  const int tid = threadIdx.x;
-  const int cnt = clampi(count[unit], 0, min(cap, ENC_SMALL_CAP));
-  if (tid < cnt) {
-    const int J = tok_pos[(size_t)unit * cap + tid];
-    const int slot = src_slot[(size_t)unit * cap + tid];
-    s_slot[tid] = (slot >= 0 && slot < src_rows) ? slot : -1;
-    unsigned sg = 0;
-    for (int i = 0; i < d.r; ++i) {
-      const int bk = bucket_of(d, i, J);
-      s_bucket[tid][i] = bk;
-      if (sign_neg(d, i, J)) sg |= 1u << i;
-      if (out_bucket) out_bucket[((size_t)unit * cap + tid) * d.r + i] = bk;
-    }
-    s_sign[tid] = sg;
-    if (out_sign) out_sign[(size_t)unit * cap + tid] = (uint8_t)sg;
-  }
-  __syncthreads();
-  const int c = tid;   // one channel per thread
-  const bool fk = (d.sign_mask & 1) != 0, fv = (d.sign_mask & 2) != 0;
-  for (int i = 0; i < d.r; ++i) {
-    for (int e = 0; e < cnt; ++e) {
-      if (s_slot[e] < 0) continue;
-      const int bk = s_bucket[e][i];
-      bool first = true;
-      for (int e2 = 0; e2 < e; ++e2) first = first && !(s_slot[e2] >= 0 && s_bucket[e2][i] == bk);
-      if (!first) continue;
-      const size_t idx = (((size_t)unit * d.r + i) * d.w + bk) * D + c;
-      float ak = Store<T>::load1(sk + idx), av = Store<T>::load1(sv + idx);
-      for (int e2 = e; e2 < cnt; ++e2) {
-        if (s_slot[e2] >= 0 && s_bucket[e2][i] == bk) {
-          const bool neg = (s_sign[e2] >> i) & 1u;
-          const size_t src = ((size_t)unit * src_rows + s_slot[e2]) * D + c;
-          const float kv = Store<T>::load1(k_src + src), vv = Store<T>::load1(v_src + src);
-          ak += (fk && neg) ? -kv : kv;
-          av += (fv && neg) ? -vv : vv;
-        }
-      }
-      Store<T>::store1(sk + idx, ak);
-      Store<T>::store1(sv + idx, av);
-    }
-  }
+  encode_small_body<T>(d, blockIdx.x, k_src, v_src, src_rows, src_slot, tok_pos, count, cap, sk, sv, out_bucket,
+                       out_sign);
 }
 
 // ------------------------------------------------------------------ bulk
@@ -229,7 +186,7 @@ static hipError_t launch_t(const DevDesc& d, const void* k_src, const void* v_sr
                            const EncodePlan& plan, hipStream_t st) {
   const int units = d.B * d.Hkv;
   if (!plan.bulk) {
-    hipLaunchKernelGGL(encode_small_kernel<T>, dim3(units), dim3(D), 0, st, d, (const T*)k_src,
+    hipLaunchKernelGGL(encode_small_kernel<T>, dim3(units), dim3(D * (d.r < 4 ? d.r : 4)), 0, st, d, (const T*)k_src,
                        (const T*)v_src, src_rows, src_slot, tok_pos, count, cap, (T*)sk, (T*)sv, out_bucket,
                        out_sign);
     return hipGetLastError();

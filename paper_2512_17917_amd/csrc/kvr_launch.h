@@ -85,6 +85,14 @@ hipError_t launch_append(const DevDesc& d, int dtype, const void* k_new, const v
                          const int32_t* n_ctx, void* k_ret, void* v_ret, int32_t* ret_pos, int ret_cap,
                          int32_t* out_slot, hipStream_t st);
 
+// append -> select -> encode of every unit in one launch (ret_cap <= 8192, evict_cap <= 64)
+hipError_t launch_step_update(const DevDesc& d, int dtype, const void* k_new, const void* v_new,
+                              const int32_t* n_ctx, void* k_ret, void* v_ret, int32_t* ret_pos, int ret_cap,
+                              const float* scores, long long n_cap, int n_recent, int k_candidate,
+                              int32_t* evict_slot, int32_t* evict_pos, int32_t* n_evict, int evict_cap,
+                              int32_t* vague_pos, int32_t* n_vague, int vague_cap, void* sk, void* sv,
+                              hipStream_t st);
+
 hipError_t launch_encode(const DevDesc& d, int dtype, const void* k_src, const void* v_src, int src_rows,
                          const int32_t* src_slot, const int32_t* tok_pos, const int32_t* count, int cap,
                          void* sk, void* sv, int32_t* out_bucket, uint8_t* out_sign,

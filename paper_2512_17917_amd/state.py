@@ -64,15 +64,28 @@ class LayerState:
                               self.ws_attend)
         return self.out
 
-    def decode_step(self, k_new, v_new, q, *, bump_n_ctx=True):
+    def step_update(self, k_new, v_new):
+        """append + select + encode in one launch (decode steady state)."""
+        kvr.kvr_step_update(self.desc, k_new, v_new, self.n_ctx, self.k_ret, self.v_ret, self.ret_pos,
+                            self.ret_cap, self.scores, self.n_cap, self.n_recent, self.k_candidate,
+                            self.evict_slot, self.evict_pos, self.n_evict, self.evict_cap, self.vague_pos,
+                            self.n_vague, self.vague_cap, self.sketch_k, self.sketch_v)
+
+    def decode_step(self, k_new, v_new, q, *, bump_n_ctx=True, fused=None):
         """append -> select -> encode -> attend.  n_ctx counts the new token from
         here on; pass bump_n_ctx=False when several layers share one n_ctx tensor
-        that the caller advances once per step."""
+        that the caller advances once per step.  fused: use kvr_step_update for the
+        first three (default: whenever its size limits allow)."""
         if bump_n_ctx:
             self.n_ctx += 1
-        self.append(k_new, v_new)
-        self.select()
-        self.encode()
+        if fused is None:
+            fused = self.ret_cap <= 8192 and self.evict_cap <= 64
+        if fused:
+            self.step_update(k_new, v_new)
+        else:
+            self.append(k_new, v_new)
+            self.select()
+            self.encode()
         return self.attend(q)
 
     # -- building the state from a prompt ---------------------------------------

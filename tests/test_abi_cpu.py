@@ -128,6 +128,16 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     # append
     assert L.kvr_append(dp, p, p, p, p, p, None, 10, None, None) == E
     assert L.kvr_append(dp, p, p, p, p, p, p, 0, None, None) == E
+    # step_update
+    ok_args = [dp, p, p, p, p, p, p, 100, p, 1000, 10, 20, p, p, p, 8, p, p, 500, p, p, None]
+    bad = list(ok_args); bad[1] = None
+    assert L.kvr_step_update(*bad) == E
+    bad = list(ok_args); bad[16] = None          # vague_pos without n_vague
+    assert L.kvr_step_update(*bad) == E
+    bad = list(ok_args); bad[7] = 9000           # more slots than the fused kernel takes
+    assert L.kvr_step_update(*bad) == kvr.KVR_ERR_UNSUPPORTED
+    bad = list(ok_args); bad[15] = 65
+    assert L.kvr_step_update(*bad) == kvr.KVR_ERR_UNSUPPORTED
     # attend
     assert L.kvr_attend_decode(dp, None, p, p, p, 10, p, p, p, p, 20, p, p, 100, p, 1 << 30, None) == E
     assert L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, None, 20, p, p, 100, p, 1 << 30, None) == E

@@ -452,12 +452,14 @@ def test_fused_equals_dense_over_kvr_reconstruct(kvr):
 
 
 # ----------------------------------------------------------------------------- whole steps
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("name", ["c1", "tiny_bf16", "tiny_r4"])
-def test_decode_steps_follow_the_oracle(kvr, LayerState, name):
+def test_decode_steps_follow_the_oracle(kvr, LayerState, name, fused):
     """Several decode steps.  Before every step the GPU state is loaded from the
     oracle's state; after it, indices and sketch must match bit for bit, floats
     within tolerance.  (Feeding each step from the oracle keeps one step's float
-    rounding from deciding the next step's integer choices.)"""
+    rounding from deciding the next step's integer choices.)  fused: append, select
+    and encode through kvr_step_update instead of the three separate calls."""
     if name == "c1":
         wl = S.WORKLOADS["c1"]
         nsteps = 3
@@ -481,7 +483,7 @@ def test_decode_steps_follow_the_oracle(kvr, LayerState, name):
         ls = U.layer_state_from_oracle(kvr, LayerState, d, states, wl.batch, wl.n_kv_heads, vague_cap=vague_cap)
         kn, vn = S.new_tokens(wl, layer, t)
         q = S.queries(wl, layer, t + 1)
-        out = ls.decode_step(kn.cuda(), vn.cuda(), q.cuda())
+        out = ls.decode_step(kn.cuda(), vn.cuda(), q.cuda(), fused=fused)
         torch.cuda.synchronize()
         og = out.cpu().double().numpy()
         ne = ls.n_evict.cpu().numpy().reshape(-1)
