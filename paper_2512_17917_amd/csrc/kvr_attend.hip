@@ -321,19 +321,43 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
 #pragma unroll
     for (int g = 0; g < G; ++g) { M[g] = sM[g]; invL[g] = sL[g] > 0.f ? 1.f / sL[g] : 0.f; }
     float* sc = a.scores + (size_t)unit * a.n_cap;
-    for (int t = blockIdx.x * 256 + tid; t < total; t += gridDim.x * 256) {
-      int pos;
-      if (t < a.ret_cap) pos = a.ret_pos ? a.ret_pos[(size_t)unit * a.ret_cap + t] : t;
-      else pos = a.vague_pos[(size_t)unit * a.vague_cap + (t - a.ret_cap)];
-      if (pos < 0 || pos >= a.n_cap) continue;
-      const float* lg = a.logits + ((size_t)unit * tot_cap + t) * G;
-      float p = 0.f;
+    // four tokens per thread and round; the loads of a round are independent
+    constexpr int U = 4;
+    for (int t0 = blockIdx.x * 256 * U + tid; t0 < total; t0 += gridDim.x * 256 * U) {
+      int pos[U];
+      float p[U], old[U];
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float x = lg[g];
-        if (x != -__builtin_inff()) p += expf(x - M[g]) * invL[g];
+      for (int u = 0; u < U; ++u) {
+        const int t = t0 + u * 256;
+        pos[u] = -1;
+        if (t < total) {
+          if (t < a.ret_cap) pos[u] = a.ret_pos ? a.ret_pos[(size_t)unit * a.ret_cap + t] : t;
+          else pos[u] = a.vague_pos[(size_t)unit * a.vague_cap + (t - a.ret_cap)];
+          if (pos[u] >= a.n_cap) pos[u] = -1;
+        }
       }
-      sc[pos] += p;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int t = min(t0 + u * 256, total - 1);
+        const float* lg = a.logits + ((size_t)unit * tot_cap + t) * G;
+        float x[G];
+        if constexpr (G == 4) {
+          const float4 v = *reinterpret_cast<const float4*>(lg);
+          x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+        } else {
+#pragma unroll
+          for (int g = 0; g < G; ++g) x[g] = lg[g];
+        }
+        old[u] = (pos[u] >= 0) ? sc[pos[u]] : 0.f;
+        float acc = 0.f;
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+          if (x[g] != -__builtin_inff()) acc += __expf(x[g] - M[g]) * invL[g];
+        p[u] = acc;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (pos[u] >= 0) sc[pos[u]] = old[u] + p[u];
     }
   }
 }

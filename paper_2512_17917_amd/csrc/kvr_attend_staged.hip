@@ -96,6 +96,34 @@ __device__ __forceinline__ uint4 xor4(uint4 v, uint32_t mask) {
   return make_uint4(v.x ^ mask, v.y ^ mask, v.z ^ mask, v.w ^ mask);
 }
 
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// (low half of a, low half of b) and (high half of a, high half of b) as one dword
+__device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pair_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+__device__ __forceinline__ short4_t pack_k4(uint32_t k01, uint32_t k23) {
+  return __builtin_bit_cast(short4_t, make_uint2(k01, k23));
+}
+template <int DW>
+__device__ __forceinline__ uint32_t dword_of(const uint4& v) {
+  return DW == 0 ? v.x : DW == 1 ? v.y : DW == 2 ? v.z : v.w;
+}
+
+// One dword position (two channels) of a piece, for the 4 tokens of a block:
+// acc[2 DW] and acc[2 DW + 1] (4 head sums each) += weights x values.
+template <int DW>
+__device__ __forceinline__ void pv_mfma(const uint4 (&med)[4], short4_t a_hi, short4_t a_lo, f32x4_t (&acc)[8]) {
+  const uint32_t t0 = dword_of<DW>(med[0]), t1 = dword_of<DW>(med[1]);
+  const uint32_t t2 = dword_of<DW>(med[2]), t3 = dword_of<DW>(med[3]);
+  const short4_t b_even = pack_k4(pair_lo(t0, t1), pair_lo(t2, t3));
+  const short4_t b_odd = pack_k4(pair_hi(t0, t1), pair_hi(t2, t3));
+  acc[2 * DW] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_hi, b_even, acc[2 * DW], 0, 0, 0);
+  acc[2 * DW] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_lo, b_even, acc[2 * DW], 0, 0, 0);
+  acc[2 * DW + 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_hi, b_odd, acc[2 * DW + 1], 0, 0, 0);
+  acc[2 * DW + 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_lo, b_odd, acc[2 * DW + 1], 0, 0, 0);
+}
+
 // Workgroup barrier for data exchanged through LDS only: waits for this wave's
 // LDS traffic, not for its outstanding global stores (which __syncthreads would).
 __device__ __forceinline__ void lds_barrier() {
@@ -395,9 +423,26 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
     for (int g = 0; g < G; ++g)
 #pragma unroll
       for (int c = 0; c < VCH; ++c) acc[g][c] = 0.f;
+    // With 4 lanes per token (CH = 64) the 4 lanes of a token group are one block
+    // of v_mfma_f32_4x4x4 (16 blocks): the group's 4 tokens of a round are the
+    // contraction index, lane `sub` supplies the weights of head `sub` (A) and
+    // one channel of the rebuilt values (B), and keeps that channel's 4 head
+    // sums (D).  The weights go in as bf16 hi + lo (two MFMAs), which carries 16
+    // mantissa bits; the values are bf16 already.  This replaces the float32
+    // multiply-adds of the vector ALUs, which are this kernel's bottleneck.
+    constexpr bool V_MFMA = (LPT == 4 && PPL == 2);
+    f32x4_t accm[V_MFMA ? 2 : 1][V_MFMA ? 8 : 1];
+    if constexpr (V_MFMA) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) accm[h][c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
 #pragma unroll
     for (int k = 0; k < ST_KMAX; ++k) {
       if (k < n_k) {
+        uint4 med[V_MFMA ? 2 : 1][V_MFMA ? 4 : 1];
+        float psel[V_MFMA ? 4 : 1];
 #pragma unroll
         for (int j8 = 0; j8 < LPT; ++j8) {
           const int owner = j8 * TPW + tl;
@@ -422,6 +467,13 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
             fm[2] = info_neg<2>(inf) ? 0x80008000u : 0u;
             if constexpr (R > 3) fm[3] = info_neg<3>(inf) ? 0x80008000u : 0u;
           }
+          if constexpr (V_MFMA) {
+            float ph = pg[0];
+            if constexpr (G > 1) ph = (sub == 1) ? pg[1] : ph;
+            if constexpr (G > 2) ph = (sub == 2) ? pg[2] : ph;
+            if constexpr (G > 3) ph = (sub == 3) ? pg[3] : ph;
+            psel[j8] = (sub < G) ? ph : 0.f;
+          }
 #pragma unroll
           for (int h = 0; h < PPL; ++h) {
             const int co = (h == 0 ? pa : pb) * 16;
@@ -432,15 +484,46 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
               if (!(R == 3 && i == 0)) row[i] = xor4(row[i], fm[i]);
             }
             const uint4 m = median_piece<R>(row, d.median_mode);
-            const float v[8] = {bf_lo(m.x), bf_hi(m.x), bf_lo(m.y), bf_hi(m.y),
-                                bf_lo(m.z), bf_hi(m.z), bf_lo(m.w), bf_hi(m.w)};
+            if constexpr (V_MFMA) {
+              med[h][j8] = m;
+            } else {
+              const float v[8] = {bf_lo(m.x), bf_hi(m.x), bf_lo(m.y), bf_hi(m.y),
+                                  bf_lo(m.z), bf_hi(m.z), bf_lo(m.w), bf_hi(m.w)};
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+              for (int g = 0; g < G; ++g)
 #pragma unroll
-              for (int c = 0; c < 8; ++c) acc[g][h * 8 + c] = fmaf(pg[g], v[c], acc[g][h * 8 + c]);
+                for (int c = 0; c < 8; ++c) acc[g][h * 8 + c] = fmaf(pg[g], v[c], acc[g][h * 8 + c]);
+            }
+          }
+        }
+        if constexpr (V_MFMA) {
+          // A: this lane's head, 4 tokens, as bf16 hi and lo parts
+          uint32_t hb[4], lb[4];
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const uint32_t pb_ = __float_as_uint(psel[t]);
+            hb[t] = pb_ & 0xffff0000u;
+            lb[t] = __float_as_uint(psel[t] - __uint_as_float(hb[t]));
+          }
+          const short4_t a_hi = pack_k4(pair_hi(hb[0], hb[1]), pair_hi(hb[2], hb[3]));
+          const short4_t a_lo = pack_k4(pair_hi(lb[0], lb[1]), pair_hi(lb[2], lb[3]));
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            pv_mfma<0>(med[h], a_hi, a_lo, accm[h]);
+            pv_mfma<1>(med[h], a_hi, a_lo, accm[h]);
+            pv_mfma<2>(med[h], a_hi, a_lo, accm[h]);
+            pv_mfma<3>(med[h], a_hi, a_lo, accm[h]);
           }
         }
       }
+    }
+    if constexpr (V_MFMA) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[g][h * 8 + c] = accm[h][c][g];
     }
     KVR_STAMP(8 + 2 * cc);
     // odd token groups hold their two pieces swapped: put them in piece order
