@@ -58,18 +58,26 @@ struct RetTile {
   int pos[4];    // position of token t0 + 4 (lane div 16) + j, -1 = empty slot / past the slice
 };
 
+// 16 bytes that are read exactly once: non-temporal, so that the stream does not
+// push the sketch (which the staged kernel reads many times) out of L2
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load16(const bf16_t* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 __device__ __forceinline__ void load_tile(RetTile& t, const bf16_t* __restrict__ kret,
                                           const bf16_t* __restrict__ vret, const int32_t* __restrict__ rp,
                                           int t0, int t_end, int ret_cap, int r16, int col) {
   const int tk = min(t0 + col, ret_cap - 1);
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
-    t.ka[kk] = *reinterpret_cast<const uint4*>(kret + (size_t)tk * D + 32 * kk + 8 * r16);
+    t.ka[kk] = stream_load16(kret + (size_t)tk * D + 32 * kk + 8 * r16);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int tt = t0 + 4 * r16 + j;
     const int tc = min(tt, ret_cap - 1);
-    t.vv[j] = *reinterpret_cast<const uint4*>(vret + (size_t)tc * D + 8 * col);
+    t.vv[j] = stream_load16(vret + (size_t)tc * D + 8 * col);
     t.pos[j] = (tt < t_end) ? (rp ? rp[tc] : tt) : -1;
   }
 }

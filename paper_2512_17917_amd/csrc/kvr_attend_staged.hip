@@ -27,183 +27,9 @@
 // mantissa, so the order of finite values is the same; zeros of either sign
 // compare equal).  The sign g_0 of row 0 is moved onto the weight, so only
 // rows 1.. need their sign bits flipped (the median is an odd function).
-#include "kvr_launch.h"
+#include "kvr_staged.h"
 
 namespace kvr {
-
-constexpr int ST_THREADS = 512;
-constexpr int ST_WAVES = 8;
-constexpr int ST_KMAX = 6;
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-
-// Development aid, compiled out unless KVR_PHASE_TIMING is defined: thread 0 of
-// every workgroup stamps the cycle counter at phase boundaries.
-#ifdef KVR_PHASE_TIMING
-__device__ unsigned long long g_phase_t[8192 * 16];
-#define KVR_STAMP(i)                                                              \
-  do {                                                                            \
-    if (threadIdx.x == 0 && blockIdx.x < 8192) g_phase_t[blockIdx.x * 16 + (i)] = clock64(); \
-  } while (0)
-#else
-#define KVR_STAMP(i) \
-  do {               \
-  } while (0)
-#endif
-
-__device__ __forceinline__ uint32_t med3_bf16x2(uint32_t a, uint32_t b, uint32_t c) {
-  uint32_t dst;
-  asm("v_med3_f16 %0, %1, %2, %3" : "=v"(dst) : "v"(a), "v"(b), "v"(c));
-  asm("v_med3_f16 %0, %1, %2, %3 op_sel:[1,1,1,1]" : "+v"(dst) : "v"(a), "v"(b), "v"(c));
-  return dst;
-}
-
-__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c,
-                                         false);
-}
-
-__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-// two floats that are exactly representable in bf16 -> packed pair
-__device__ __forceinline__ uint32_t pack_bf16_exact(float lo, float hi) {
-  return (__float_as_uint(hi) & 0xffff0000u) | (__float_as_uint(lo) >> 16);
-}
-
-template <int R>
-__device__ __forceinline__ uint32_t median_dword(const uint32_t (&x)[R], int mode) {
-  if constexpr (R == 3) {
-    return med3_bf16x2(x[0], x[1], x[2]);
-  } else {
-    float lo[R], hi[R];
-#pragma unroll
-    for (int i = 0; i < R; ++i) { lo[i] = bf_lo(x[i]); hi[i] = bf_hi(x[i]); }
-    return pack_bf16_exact(median_rows<R, bf16_t>(lo, R, mode), median_rows<R, bf16_t>(hi, R, mode));
-  }
-}
-
-// Median over R rows of a 16-byte piece (8 packed bf16 channels).
-template <int R>
-__device__ __forceinline__ uint4 median_piece(const uint4 (&row)[R], int mode) {
-  uint32_t x[R], y[R], z[R], w_[R];
-#pragma unroll
-  for (int i = 0; i < R; ++i) { x[i] = row[i].x; y[i] = row[i].y; z[i] = row[i].z; w_[i] = row[i].w; }
-  return make_uint4(median_dword<R>(x, mode), median_dword<R>(y, mode), median_dword<R>(z, mode),
-                    median_dword<R>(w_, mode));
-}
-
-__device__ __forceinline__ uint4 xor4(uint4 v, uint32_t mask) {
-  return make_uint4(v.x ^ mask, v.y ^ mask, v.z ^ mask, v.w ^ mask);
-}
-
-typedef short short4_t __attribute__((ext_vector_type(4)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
-// (low half of a, low half of b) and (high half of a, high half of b) as one dword
-__device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
-__device__ __forceinline__ uint32_t pair_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
-__device__ __forceinline__ short4_t pack_k4(uint32_t k01, uint32_t k23) {
-  return __builtin_bit_cast(short4_t, make_uint2(k01, k23));
-}
-template <int DW>
-__device__ __forceinline__ uint32_t dword_of(const uint4& v) {
-  return DW == 0 ? v.x : DW == 1 ? v.y : DW == 2 ? v.z : v.w;
-}
-
-// One dword position (two channels) of a piece, for the 4 tokens of a block:
-// acc[2 DW] and acc[2 DW + 1] (4 head sums each) += weights x values.
-template <int DW>
-__device__ __forceinline__ void pv_mfma(const uint4 (&med)[4], short4_t a_hi, short4_t a_lo, f32x4_t (&acc)[8]) {
-  const uint32_t t0 = dword_of<DW>(med[0]), t1 = dword_of<DW>(med[1]);
-  const uint32_t t2 = dword_of<DW>(med[2]), t3 = dword_of<DW>(med[3]);
-  const short4_t b_even = pack_k4(pair_lo(t0, t1), pair_lo(t2, t3));
-  const short4_t b_odd = pack_k4(pair_hi(t0, t1), pair_hi(t2, t3));
-  acc[2 * DW] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_hi, b_even, acc[2 * DW], 0, 0, 0);
-  acc[2 * DW] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_lo, b_even, acc[2 * DW], 0, 0, 0);
-  acc[2 * DW + 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_hi, b_odd, acc[2 * DW + 1], 0, 0, 0);
-  acc[2 * DW + 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_lo, b_odd, acc[2 * DW + 1], 0, 0, 0);
-}
-
-// Workgroup barrier for data exchanged through LDS only: waits for this wave's
-// LDS traffic, not for its outstanding global stores (which __syncthreads would).
-__device__ __forceinline__ void lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
-}
-// Sum over the lanes of a 16-lane row whose lane numbers are equal modulo LPT
-// (row rotations by LPT, 2 LPT, ..., 8); every lane ends up with its class's sum.
-template <int LPT>
-__device__ __forceinline__ float row_sum(float x) {
-  if constexpr (LPT <= 1) x = dpp_add<0x121>(x);
-  if constexpr (LPT <= 2) x = dpp_add<0x122>(x);
-  if constexpr (LPT <= 4) x = dpp_add<0x124>(x);
-  return dpp_add<0x128>(x);
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_max(float x) {
-  return fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false)));
-}
-// maximum over the 16 lanes of a row, in every lane
-__device__ __forceinline__ float row_max(float x) {
-  x = dpp_max<0x121>(x);
-  x = dpp_max<0x122>(x);
-  x = dpp_max<0x124>(x);
-  return dpp_max<0x128>(x);
-}
-
-// token info: 4 x 16 bits; bits 0..14 = LDS row index (i * w + h_i(J)), bit 15 = 1 iff g_i(J) = -1
-template <int I>
-__device__ __forceinline__ uint32_t info_row(uint2 inf) {
-  const uint32_t wd = (I < 2) ? inf.x : inf.y;
-  return (I & 1) ? __builtin_amdgcn_ubfe(wd, 16, 15) : (wd & 0x7fffu);
-}
-template <int I>
-__device__ __forceinline__ uint32_t info_neg(uint2 inf) {
-  const uint32_t wd = (I < 2) ? inf.x : inf.y;
-  return __builtin_amdgcn_ubfe(wd, (I & 1) * 16 + 15, 1);
-}
-// 0x80008000 if the signs of rows I and 0 differ, else 0
-template <int I>
-__device__ __forceinline__ uint32_t info_flipmask(uint2 inf) {
-  const uint32_t wd = (I < 2) ? inf.x : inf.y;
-  const uint32_t x = wd ^ (inf.x << ((I & 1) * 16));      // bit (I&1)*16+15 = sign_I ^ sign_0
-  return (uint32_t)__builtin_amdgcn_sbfe(x, (I & 1) * 16 + 15, 1) & 0x80008000u;
-}
-
-template <int R>
-__device__ __forceinline__ void row_offsets(uint2 inf, int (&rb)[R], int rowb_log2) {
-  rb[0] = (int)(info_row<0>(inf) << rowb_log2);
-  if constexpr (R > 1) rb[1] = (int)(info_row<1>(inf) << rowb_log2);
-  if constexpr (R > 2) rb[2] = (int)(info_row<2>(inf) << rowb_log2);
-  if constexpr (R > 3) rb[3] = (int)(info_row<3>(inf) << rowb_log2);
-}
-
-// Copy channel chunk `cc` of a sketch tensor [rows][128] (bf16, global) into LDS
-// rows of ROWB bytes with global->LDS loads that bypass the registers
-// (global_load_lds_dwordx4: lane i's 16 bytes land at the wave's LDS base +
-// 16 i).  Piece p of the chunk lives at LDS offset 16 p, so a wave that takes 64
-// consecutive pieces fills 1 KB of consecutive LDS.  All copies of a wave are
-// in flight together; the caller's barrier must follow the vmcnt wait done here.
-// Tail lanes re-read the last piece into the padding behind the chunk (the
-// buffer is sized to a multiple of 1 KB).
-template <int NC, int ROWB>
-__device__ __forceinline__ void stage_chunk(const unsigned char* __restrict__ g, unsigned char* s_sk,
-                                            int n_pieces, int cc, int tid) {
-  const int lane = tid & 63, wave = tid >> 6;
-  for (int p0 = wave * 64; p0 < n_pieces; p0 += ST_THREADS) {
-    const int idx = min(p0 + lane, n_pieces - 1);
-    const int row = idx / NC, c = idx % NC;
-    __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(g + (size_t)row * (D * 2) + cc * ROWB + c * 16),
-        (__attribute__((address_space(3))) void*)(s_sk + p0 * 16), 16, 0, 0);
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
 
 template <int G, int R, int CH>
 __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc d, AttendArgs a) {
@@ -259,7 +85,6 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   }
 
   // ---- hash every token once; q to LDS ---------------------------------------
-  KVR_STAMP(0);
   uint2 info[ST_KMAX];
   uint32_t vmask = 0;
   const int32_t* vpos = a.vague_pos + (size_t)unit * a.vague_cap;
@@ -291,7 +116,6 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   const int n_pieces = R * w * NC;
 
   // ---- K phases: logits -----------------------------------------------------
-  KVR_STAMP(1);
   float s[ST_KMAX][G];
 #pragma unroll
   for (int k = 0; k < ST_KMAX; ++k)
@@ -302,7 +126,6 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
     lds_barrier();
     stage_chunk<NC, ROWB>(skg, s_sk, n_pieces, cc, tid);
     lds_barrier();
-    KVR_STAMP(2 + 2 * cc);
     // the pieces of a row are taken in two halves so that only half of q (in
     // this lane's rotated order) has to sit in registers at a time
     constexpr int JH = (NC >= 8) ? NC / 2 : NC;
@@ -338,7 +161,6 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
         }
       }
     }
-    KVR_STAMP(3 + 2 * cc);
   }
 
   // ---- softmax weights against the workgroup's own maximum -------------------
@@ -408,7 +230,6 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
   }
 
   // ---- V phases: weighted values ------------------------------------------------
-  KVR_STAMP(6);
   const int sub = lane % LPT, tl = lane / LPT;
   // the two pieces of this lane: odd token groups take them in the opposite order
   const int pa = (PPL == 2) ? sub + ((tl & 1) ? LPT : 0) : sub;
@@ -417,7 +238,6 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
     lds_barrier();
     stage_chunk<NC, ROWB>(svg, s_sk, n_pieces, cc, tid);
     lds_barrier();
-    KVR_STAMP(7 + 2 * cc);
     float acc[G][VCH];
 #pragma unroll
     for (int g = 0; g < G; ++g)
@@ -525,7 +345,6 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
 #pragma unroll
           for (int c = 0; c < 8; ++c) acc[g][h * 8 + c] = accm[h][c][g];
     }
-    KVR_STAMP(8 + 2 * cc);
     // odd token groups hold their two pieces swapped: put them in piece order
     if constexpr (PPL == 2) {
       const bool odd = (tl & 1) != 0;
@@ -567,14 +386,8 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
       a.part_o[part * G * D + (idx / CH) * D + cc * CH + (idx % CH)] = o;
     }
   }
-  KVR_STAMP(11);
 }
 
-#ifdef KVR_PHASE_TIMING
-extern "C" int kvr_debug_phase_times(unsigned long long* host_out, int n_words) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_phase_t), (size_t)n_words * 8, 0, hipMemcpyDeviceToHost);
-}
-#endif
 
 template <int G, int R, int CH>
 static hipError_t launch_one(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
@@ -612,6 +425,7 @@ static hipError_t launch_r(const DevDesc& d, const AttendArgs& a, const AttendPl
 
 hipError_t launch_attend_vague_staged(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
                                       hipStream_t st) {
+  if (d.r == 3 && plan.ch == 64) return launch_attend_vague_staged64(d, a, plan, st);
   switch (d.G) {
     case 1: return launch_r<1>(d, a, plan, st);
     case 2: return launch_r<2>(d, a, plan, st);

@@ -1,0 +1,595 @@
+// Staged attention kernel over the Vague list, specialised for r = 3 sketch rows
+// and a sketch narrow enough that 64 channels of all 3 w slots fit into LDS at
+// once (the common case: w <= ~320).  Same contract and the same token -> wave
+// mapping as the general staged kernel (kvr_attend_staged.hip); what differs:
+//
+//  * LDS latency is hidden inside each wave.  A workgroup owns its CU's LDS, so
+//    only two waves share a SIMD and they cannot cover each other's LDS round
+//    trips; every loop over pieces therefore runs as a software pipeline that
+//    keeps the row reads of the next two pieces in flight while the medians and
+//    dot products of the current one are computed.
+//  * V phases work on quads: lanes 4t .. 4t+3 rebuild the 4 tokens that these
+//    same lanes own (one piece per lane and pass, two passes), so a token's
+//    hashes reach the quad by DPP quad broadcasts and its softmax weights are
+//    brought into matrix-core operand form (4x4 transpose inside the quad,
+//    sign g_0 folded in, bf16 hi + lo split) once, after the softmax, instead
+//    of once per token and phase.  No LDS copy of the hashes is needed.
+//  * Copies overlap: the first K chunk is fetched while the hashes are
+//    computed, the first V chunk during the softmax, the second V chunk during
+//    the reduction of the first (which has LDS scratch of its own).
+#include "kvr_staged.h"
+
+namespace kvr {
+
+// Development aid, compiled out unless KVR_PHASE_TIMING is defined: lane 0 of
+// every wave stamps the cycle counter at phase boundaries.
+#ifdef KVR_PHASE_TIMING
+__device__ unsigned long long g_phase_t[2048 * 8 * 16];
+#define KVR_STAMP(i)                                                              \
+  do {                                                                            \
+    if ((threadIdx.x & 63) == 0 && blockIdx.x < 2048)                             \
+      g_phase_t[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (i)] = clock64();    \
+  } while (0)
+#else
+#define KVR_STAMP(i) \
+  do {               \
+  } while (0)
+#endif
+
+struct Rows3 {
+  uint4 r0, r1, r2;
+};
+
+__device__ __forceinline__ void load_rows3(Rows3& o, const unsigned char* s_sk, const int (&rb)[3], int co) {
+  o.r0 = *reinterpret_cast<const uint4*>(s_sk + rb[0] + co);
+  o.r1 = *reinterpret_cast<const uint4*>(s_sk + rb[1] + co);
+  o.r2 = *reinterpret_cast<const uint4*>(s_sk + rb[2] + co);
+}
+
+__device__ __forceinline__ uint4 median3(const Rows3& x) {
+  return make_uint4(med3_bf16x2(x.r0.x, x.r1.x, x.r2.x), med3_bf16x2(x.r0.y, x.r1.y, x.r2.y),
+                    med3_bf16x2(x.r0.z, x.r1.z, x.r2.z), med3_bf16x2(x.r0.w, x.r1.w, x.r2.w));
+}
+
+// value of lane J of this lane's quad
+template <int J>
+__device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, J | (J << 2) | (J << 4) | (J << 6), 0xf, 0xf, false);
+}
+template <int J>
+__device__ __forceinline__ float quad_bcast_f(float v) {
+  return __uint_as_float(quad_bcast<J>(__float_as_uint(v)));
+}
+
+// value of lane (l ^ 4): neighbouring quads trade (row rotations by 12 and by 4,
+// each written into the lanes where it is the wanted direction)
+__device__ __forceinline__ float xchg4(float x) {
+  const int v = __float_as_int(x);
+  int r = __builtin_amdgcn_update_dpp(v, v, 0x12C, 0xf, 0x5, false);   // lanes 0-3, 8-11 of a row
+  r = __builtin_amdgcn_update_dpp(r, v, 0x124, 0xf, 0xa, false);       // lanes 4-7, 12-15
+  return __int_as_float(r);
+}
+
+// V phases: the rows of one piece of token J of the quad, plus the masks that
+// flip rows 1 and 2 relative to row 0
+struct VItem {
+  Rows3 rows;
+  uint32_t fm1, fm2;
+};
+
+template <int J>
+__device__ __forceinline__ void v_fetch(VItem& o, uint2 inf_own, const unsigned char* s_sk, int co) {
+  const uint2 inf = make_uint2(quad_bcast<J>(inf_own.x), quad_bcast<J>(inf_own.y));
+  int rb[3];
+  row_offsets<3>(inf, rb, 7);
+  o.fm1 = info_flipmask<1>(inf);
+  o.fm2 = info_flipmask<2>(inf);
+  load_rows3(o.rows, s_sk, rb, co);
+}
+
+__device__ __forceinline__ uint4 v_median(const VItem& it) {
+  Rows3 x;
+  x.r0 = it.rows.r0;
+  x.r1 = xor4(it.rows.r1, it.fm1);
+  x.r2 = xor4(it.rows.r2, it.fm2);
+  return median3(x);
+}
+
+// acc[c] (4 head sums of channel c of the piece) += weights (4 heads x 4 tokens,
+// bf16 hi + lo) x values (4 tokens x 8 channels).  All hi products first, so
+// that two matrix instructions on one accumulator are 8 instructions apart.
+__device__ __forceinline__ void pv_piece(const uint4 (&med)[4], short4_t a_hi, short4_t a_lo, f32x4_t (&acc)[8]) {
+  short4_t be[4], bo[4];
+  be[0] = pack_k4(pair_lo(med[0].x, med[1].x), pair_lo(med[2].x, med[3].x));
+  bo[0] = pack_k4(pair_hi(med[0].x, med[1].x), pair_hi(med[2].x, med[3].x));
+  be[1] = pack_k4(pair_lo(med[0].y, med[1].y), pair_lo(med[2].y, med[3].y));
+  bo[1] = pack_k4(pair_hi(med[0].y, med[1].y), pair_hi(med[2].y, med[3].y));
+  be[2] = pack_k4(pair_lo(med[0].z, med[1].z), pair_lo(med[2].z, med[3].z));
+  bo[2] = pack_k4(pair_hi(med[0].z, med[1].z), pair_hi(med[2].z, med[3].z));
+  be[3] = pack_k4(pair_lo(med[0].w, med[1].w), pair_lo(med[2].w, med[3].w));
+  bo[3] = pack_k4(pair_hi(med[0].w, med[1].w), pair_hi(med[2].w, med[3].w));
+#pragma unroll
+  for (int dw = 0; dw < 4; ++dw) {
+    acc[2 * dw] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_hi, be[dw], acc[2 * dw], 0, 0, 0);
+    acc[2 * dw + 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_hi, bo[dw], acc[2 * dw + 1], 0, 0, 0);
+  }
+#pragma unroll
+  for (int dw = 0; dw < 4; ++dw) {
+    acc[2 * dw] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_lo, be[dw], acc[2 * dw], 0, 0, 0);
+    acc[2 * dw + 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a_lo, bo[dw], acc[2 * dw + 1], 0, 0, 0);
+  }
+}
+
+// The same value, but the compiler can no longer tell: whatever is derived from
+// it is computed where it is used instead of once per kernel and kept in
+// registers through all phases (the row offsets of every round would be).
+__device__ __forceinline__ uint2 opaque(uint2 v) {
+  asm volatile("" : "+v"(v.x), "+v"(v.y));
+  return v;
+}
+
+// Nothing may be moved across this point by the instruction scheduler: keeps the
+// row reads of later pieces ahead of the arithmetic of the current one.
+#define KVR_PIN() __builtin_amdgcn_sched_barrier(0)
+
+// The two waves that share a SIMD take turns in having the higher issue
+// priority, round by round (turn is even for one of them and odd for the
+// other).  Left alone, the older wave wins every arbitration, finishes a phase
+// far ahead of the younger one and idles at the barrier while the younger one
+// runs alone, with nobody to cover its latencies.
+// Both levels are above the default 0, at which the retained-slot kernel runs
+// when it shares the CU: its waves stream from HBM and need few issue slots, and
+// every slot they win from a wave of this kernel delays a whole workgroup at the
+// next barrier.
+__device__ __forceinline__ void take_turn(int t) {
+  if (t & 1) __builtin_amdgcn_s_setprio(2);
+  else __builtin_amdgcn_s_setprio(1);
+}
+
+// K phase on the matrix cores.  One lane = one token; v_mfma_f32_4x4x4 works on
+// blocks of 4 lanes and multiplies a 4 x 4 matrix A (row i from lane i of the
+// block: here 4 channels of q for head i) with B (column j from lane j: 4
+// channels of the token rebuilt by lane j); lane j receives the 4 head sums of
+// its token.  All columns of a block must therefore hold the same channels,
+// while LDS wants neighbouring lanes on different 16-byte pieces.  Compromise:
+// the two lanes of a pair share the piece ((lane / 2 + step) mod 8), so 16
+// neighbouring lanes still cover all 8 pieces (and the 2 x 8 bank groups of
+// the 256-byte LDS line, unless both tokens of a pair sit in rows of equal
+// parity), and every block issues each product twice, once with q for the
+// piece of its first pair and once for its second pair; a lane keeps the sum
+// that was formed with its own pair's channels.
+//
+// qx[j]: q of head (lane mod 4) for the piece that the block's first pair reads
+// at step j; the second pair reads the piece one further, i.e. qx[(j + 1) mod 8].
+template <int NK, int G>
+__device__ __forceinline__ void k_pass(const unsigned char* s_sk, const uint2 (&info)[ST_KMAX],
+                                       const uint4 (&qx)[8], const int (&co)[8], bool second_pair,
+                                       int turn, float (&s)[ST_KMAX][G]) {
+  // Three-stage pipeline over the steps t = 8 k + j of all rounds: at step t the
+  // rows of step t + 3 are requested, the medians of step t + 1 are formed, and
+  // the matrix instructions of step t run on medians formed one step earlier.
+  // (The medians come out of inline assembly, whose register writes the
+  // compiler's hazard logic does not see as vector-ALU writes: a matrix
+  // instruction right behind them read a stale operand.  Here at least a whole
+  // step lies between the two.)
+  Rows3 buf[3];                          // rows of step t live in buf[t % 3]
+  int rb[3];
+  row_offsets<3>(opaque(info[0]), rb, 7);
+  load_rows3(buf[0], s_sk, rb, co[0]);
+  load_rows3(buf[1], s_sk, rb, co[1]);
+  load_rows3(buf[2], s_sk, rb, co[2]);
+  uint4 m_cur = median3(buf[0]);
+#pragma unroll
+  for (int k = 0; k < NK; ++k) {
+    int rn[3] = {0, 0, 0};
+    if (k + 1 < NK) row_offsets<3>(opaque(info[k + 1]), rn, 7);
+    f32x4_t ax = {0.f, 0.f, 0.f, 0.f}, ay = {0.f, 0.f, 0.f, 0.f};
+    take_turn(k + turn);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int t = 8 * k + j;
+      if (j < 5) load_rows3(buf[(t + 3) % 3], s_sk, rb, co[j + 3]);
+      else if (k + 1 < NK) load_rows3(buf[(t + 3) % 3], s_sk, rn, co[j - 5]);
+      KVR_PIN();
+      uint4 m_next = m_cur;
+      if (j < 7 || k + 1 < NK) m_next = median3(buf[(t + 1) % 3]);
+      KVR_PIN();
+      const short4_t b_lo = pack_k4(m_cur.x, m_cur.y), b_hi = pack_k4(m_cur.z, m_cur.w);
+      const uint4 qa = qx[j], qb = qx[(j + 1) & 7];
+      ax = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pack_k4(qa.x, qa.y), b_lo, ax, 0, 0, 0);
+      ay = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pack_k4(qb.x, qb.y), b_lo, ay, 0, 0, 0);
+      ax = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pack_k4(qa.z, qa.w), b_hi, ax, 0, 0, 0);
+      ay = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pack_k4(qb.z, qb.w), b_hi, ay, 0, 0, 0);
+      KVR_PIN();
+      m_cur = m_next;
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) s[k][g] += second_pair ? ay[g] : ax[g];
+    rb[0] = rn[0]; rb[1] = rn[1]; rb[2] = rn[2];
+  }
+  __builtin_amdgcn_s_setprio(1);
+}
+
+// One V pass over NK rounds for the piece at byte offset co of each row: the
+// quad's 4 tokens per round, same pipeline, then the matrix instructions.
+template <int NK>
+__device__ __forceinline__ void v_pass(const unsigned char* s_sk, const uint2 (&info)[ST_KMAX],
+                                       const uint32_t (&W)[ST_KMAX][4], int co, int turn, f32x4_t (&acc)[8]) {
+  VItem buf[4];
+  v_fetch<0>(buf[0], info[0], s_sk, co);
+  v_fetch<1>(buf[1], info[0], s_sk, co);
+#pragma unroll
+  for (int k = 0; k < NK; ++k) {
+    uint4 med[4];
+    take_turn(k + turn);
+    v_fetch<2>(buf[2], info[k], s_sk, co);
+    KVR_PIN();
+    med[0] = v_median(buf[0]);
+    KVR_PIN();
+    v_fetch<3>(buf[3], info[k], s_sk, co);
+    KVR_PIN();
+    med[1] = v_median(buf[1]);
+    KVR_PIN();
+    if (k + 1 < NK) v_fetch<0>(buf[0], info[k + 1 < NK ? k + 1 : k], s_sk, co);
+    KVR_PIN();
+    med[2] = v_median(buf[2]);
+    KVR_PIN();
+    if (k + 1 < NK) v_fetch<1>(buf[1], info[k + 1 < NK ? k + 1 : k], s_sk, co);
+    KVR_PIN();
+    med[3] = v_median(buf[3]);
+    pv_piece(med, pack_k4(W[k][0], W[k][1]), pack_k4(W[k][2], W[k][3]), acc);
+    KVR_PIN();
+  }
+  __builtin_amdgcn_s_setprio(1);
+}
+
+// the round count is uniform over a wave: one scalar branch into straight-line code
+#define KVR_DISPATCH_NK(n, CALL) \
+  switch (n) {                   \
+    case 1: { constexpr int NK = 1; CALL; } break; \
+    case 2: { constexpr int NK = 2; CALL; } break; \
+    case 3: { constexpr int NK = 3; CALL; } break; \
+    case 4: { constexpr int NK = 4; CALL; } break; \
+    case 5: { constexpr int NK = 5; CALL; } break; \
+    case 6: { constexpr int NK = 6; CALL; } break; \
+    default: break;              \
+  }
+static_assert(ST_KMAX == 6, "KVR_DISPATCH_NK covers 1..6 rounds");
+
+template <int G>
+// Register cap: 184 per lane (the attribute counts in units of two on this target).  Two
+// waves of this kernel and one wave of the retained-slot kernel then fit a SIMD's 512
+// registers together, which is what lets the two kernels run side by side on a CU.
+__global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) void attend_vague_staged64_kernel(
+    DevDesc d, AttendArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int R = 3, CH = 64, NC = 8, ROWB = 128, ROWB_LOG2 = 7, NPH = D / CH, KMAX = ST_KMAX;
+  constexpr int NROW = ST_WAVES * 4;         // 16-lane rows per workgroup
+
+  // XCD-aware mapping: workgroup ids are dealt round-robin to the 8 XCDs, so all
+  // workgroups of a unit get ids that are equal modulo 8 (they share one L2).
+  const int lin = blockIdx.x;
+  const int xcd = lin & 7, jj = lin >> 3;
+  const int unit = (jj / a.n_vslices) * 8 + xcd;
+  const int vs = jj % a.n_vslices;
+  const int units = d.B * d.Hkv;
+  if (unit >= units) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = unit / d.Hkv, hk = unit % d.Hkv;
+  const int w = d.w;
+  const int sk_bytes = (R * w * ROWB + 1023) & ~1023;
+  unsigned char* s_sk = smem;                                             // one 64-channel chunk
+  float* s_part = reinterpret_cast<float*>(smem + sk_bytes);              // [NROW][G][CH]
+  float* s_stat = s_part + NROW * G * CH;                                 // [2][NROW][G]
+  uint4* s_q = reinterpret_cast<uint4*>(s_stat + 2 * NROW * G);           // [G][16]
+
+  const int nv = clampi(a.n_vague[unit], 0, a.vague_cap);
+  const int rounds_total = (nv + 63) >> 6;
+  const int NWT = a.n_vslices * ST_WAVES;
+  const int gw = vs * ST_WAVES + wave;
+  int n_k = gw < rounds_total ? (rounds_total - gw + NWT - 1) / NWT : 0;
+  if (n_k > KMAX) n_k = KMAX;             // cannot happen when the plan was made for vague_cap
+  n_k = __builtin_amdgcn_readfirstlane(n_k);      // equal in all lanes of a wave; now the compiler knows
+  const int turn = __builtin_amdgcn_readfirstlane(wave >> 2);   // waves i and i + 4 share a SIMD
+
+  const size_t sk_unit = (size_t)unit * R * w * D;      // elements
+  const unsigned char* skg = reinterpret_cast<const unsigned char*>((const bf16_t*)a.sk + sk_unit);
+  const unsigned char* svg = reinterpret_cast<const unsigned char*>((const bf16_t*)a.sv + sk_unit);
+  const int n_pieces = R * w * NC;
+
+  KVR_STAMP(0);
+  __builtin_amdgcn_s_setprio(1);
+  // ---- loads first: Vague positions of this wave's tokens, q, and a touch of
+  //      this workgroup's share of the unit's two sketches (so that the later
+  //      chunks' lines are in L2 when their turn comes) ----------------------------
+  int Jv[KMAX];
+  const int32_t* vpos = a.vague_pos + (size_t)unit * a.vague_cap;
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) {
+    const int tok = (gw + k * NWT) * 64 + lane;
+    Jv[k] = (k < n_k && tok < nv) ? vpos[tok] : -1;
+  }
+  uint4 qv = make_uint4(0u, 0u, 0u, 0u);
+  if (tid < G * 16)
+    qv = reinterpret_cast<const uint4*>((const bf16_t*)a.q + ((size_t)b * d.Hq + (size_t)hk * G) * D)[tid];
+  uint32_t touched = 0;
+  {
+    const int n_lines = 2 * R * w;                     // 128-byte lines per tensor
+    const int per_wg = (2 * n_lines + a.n_vslices - 1) / a.n_vslices;
+    const int li = vs * per_wg + tid;
+    if (tid < per_wg && li < 2 * n_lines) {
+      const bf16_t* base = (li < n_lines) ? (const bf16_t*)a.sk : (const bf16_t*)a.sv;
+      const int l2 = (li < n_lines) ? li : li - n_lines;
+      touched = *reinterpret_cast<const uint32_t*>(base + (size_t)unit * R * w * D + (size_t)l2 * 64);
+    }
+  }
+  // Wait for them here (vmcnt(0), as an instruction the compiler's wait-count
+  // bookkeeping sees), so that the hashes below do not have to wait for the
+  // chunk copy that is started next: memory operations complete in order.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+
+  // ---- the first K chunk is on its way while the hashes are computed ----------
+  stage_issue<NC, ROWB>(skg, s_sk, n_pieces, 0, tid);
+
+  // ---- hash every token once (kept in registers); q to LDS -------------------
+  uint2 info[KMAX];
+  uint32_t vmask = 0;
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) {
+    const int J = Jv[k];
+    uint2 pk = make_uint2(0u, 0u);
+    if (J >= 0) {
+      uint32_t f[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int i = 0; i < R; ++i)
+        f[i] = (uint32_t)(i * w + bucket_of(d, i, J)) | (sign_neg(d, i, J) ? 0x8000u : 0u);
+      pk = make_uint2(f[0] | (f[1] << 16), f[2] | (f[3] << 16));
+      vmask |= 1u << k;
+    }
+    info[k] = pk;
+  }
+  if (touched == 0x7fc1u && nv < 0) vmask = 0;       // never true; keeps the touch load alive
+  if (tid < G * 16) s_q[tid] = qv;
+  KVR_STAMP(1);
+  stage_wait();
+  lds_barrier();
+
+  // ---- K phases: logits -----------------------------------------------------
+  float s[KMAX][G];
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+    for (int g = 0; g < G; ++g) s[k][g] = 0.f;
+
+  for (int cc = 0; cc < NPH; ++cc) {
+    if (cc > 0) {
+      lds_barrier();
+      stage_issue<NC, ROWB>(skg, s_sk, n_pieces, cc, tid);
+      stage_wait();
+      lds_barrier();
+    }
+    KVR_STAMP(2 + 2 * cc);
+    {
+      const int head = lane & 3, pair = lane >> 1, blk2 = (lane >> 2) * 2;
+      uint4 qx[8];
+      int co[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        co[j] = ((pair + j) & 7) * 16;
+        qx[j] = (head < G) ? s_q[head * 16 + cc * NC + ((blk2 + j) & 7)] : make_uint4(0u, 0u, 0u, 0u);
+      }
+      const bool second_pair = (lane & 2) != 0;
+      KVR_DISPATCH_NK(n_k, (k_pass<NK, G>(s_sk, info, qx, co, second_pair, turn, s)))
+    }
+    KVR_STAMP(3 + 2 * cc);
+  }
+
+  // ---- the first V chunk is on its way during the softmax ----------------------
+  lds_barrier();                           // every wave is done with the K chunk
+  stage_issue<NC, ROWB>(svg, s_sk, n_pieces, 0, tid);
+
+  // ---- softmax weights against the workgroup's own maximum -------------------
+  const int tot_cap = a.ret_cap + a.vague_cap;
+  float mx[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) mx[g] = -__builtin_inff();
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) {
+    const bool valid = (vmask >> k) & 1u;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      s[k][g] = valid ? s[k][g] * d.scale : -__builtin_inff();
+      mx[g] = fmaxf(mx[g], s[k][g]);
+    }
+    if (a.logits != nullptr && valid) {
+      const int tok = (gw + k * NWT) * 64 + lane;
+      float* lg = a.logits + ((size_t)unit * tot_cap + a.ret_cap + tok) * G;
+      if constexpr (G == 4) {
+        *reinterpret_cast<float4*>(lg) = make_float4(s[k][0], s[k][1], s[k][2], s[k][3]);
+      } else {
+#pragma unroll
+        for (int g = 0; g < G; ++g) lg[g] = s[k][g];
+      }
+    }
+  }
+  // maxima and sums: DPP inside each 16-lane row, the NROW rows of the
+  // workgroup meet in LDS, and every wave folds the NROW values again with one
+  // read per head (lane l takes row l mod 32), a row reduction and one exchange
+  // between the two row pairs
+  const int prow = wave * 4 + (lane >> 4);
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    mx[g] = row_max(mx[g]);
+    if ((lane & 15) == 0) s_stat[prow * G + g] = mx[g];
+  }
+  lds_barrier();
+  float lsum[G], M[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float x = row_max(s_stat[(lane & (NROW - 1)) * G + g]);
+    M[g] = fmaxf(x, __shfl_xor(x, 16));
+    lsum[g] = 0.f;
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      const float p = (s[k][g] == -__builtin_inff()) ? 0.f : __expf(s[k][g] - M[g]);
+      s[k][g] = p;                 // from here on s holds the weights
+      lsum[g] += p;
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    lsum[g] = row_sum<1>(lsum[g]);
+    if ((lane & 15) == 0) s_stat[NROW * G + prow * G + g] = lsum[g];
+  }
+  lds_barrier();
+  const size_t part = (size_t)unit * a.n_slices + a.n_rslices + vs;
+  if (wave == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float x = row_sum<1>(s_stat[NROW * G + (lane & (NROW - 1)) * G + g]);
+      x += __shfl_xor(x, 16);
+      if (lane == 0) {
+        a.part_ml[(part * G + g) * 2] = M[g];
+        a.part_ml[(part * G + g) * 2 + 1] = x;
+      }
+    }
+  }
+
+  // ---- weights into matrix-core operand form ----------------------------------
+  // Lane `sub` of quad t needs, for the quad's 4 tokens, the weight of head
+  // `sub` (zero if there is no such head), with the sign g_0 of the token folded
+  // in: a 4x4 transpose inside the quad.  Split into bf16 hi + lo (16 mantissa
+  // bits together) and packed as the two A operands of a round.
+  const int sub = lane & 3, tl = lane >> 2;
+  uint32_t W[KMAX][4];
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) {
+    const uint32_t sgn = (info[k].x << 16) & 0x80000000u;
+    float pf[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) pf[g] = __uint_as_float(__float_as_uint(s[k][g]) ^ sgn);
+    float T[4];
+#define KVR_TRANSPOSE_COL(J)                                          \
+  {                                                                   \
+    float t = quad_bcast_f<J>(pf[0]);                                 \
+    if constexpr (G > 1) { const float u = quad_bcast_f<J>(pf[1]); t = (sub == 1) ? u : t; } \
+    if constexpr (G > 2) { const float u = quad_bcast_f<J>(pf[2]); t = (sub == 2) ? u : t; } \
+    if constexpr (G > 3) { const float u = quad_bcast_f<J>(pf[3]); t = (sub == 3) ? u : t; } \
+    T[J] = (sub < G) ? t : 0.f;                                       \
+  }
+    KVR_TRANSPOSE_COL(0)
+    KVR_TRANSPOSE_COL(1)
+    KVR_TRANSPOSE_COL(2)
+    KVR_TRANSPOSE_COL(3)
+#undef KVR_TRANSPOSE_COL
+    uint32_t hb[4], lb[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      hb[t] = __float_as_uint(T[t]) & 0xffff0000u;
+      lb[t] = __float_as_uint(T[t] - __uint_as_float(hb[t]));
+    }
+    W[k][0] = pair_hi(hb[0], hb[1]);
+    W[k][1] = pair_hi(hb[2], hb[3]);
+    W[k][2] = pair_hi(lb[0], lb[1]);
+    W[k][3] = pair_hi(lb[2], lb[3]);
+  }
+
+  // ---- V phases: weighted values ------------------------------------------------
+  KVR_STAMP(6);
+  // the two pieces of this lane: odd quads take them in the opposite order, so
+  // that 8 neighbouring lanes always cover 8 different 16-byte bank groups
+  const int pa = sub + ((tl & 1) ? 4 : 0);
+  const int pb = sub + ((tl & 1) ? 0 : 4);
+  for (int cc = 0; cc < NPH; ++cc) {
+    stage_wait();
+    lds_barrier();
+    KVR_STAMP(7 + 2 * cc);
+    // One accumulator set serves both passes.  Pass 0 sums piece pa of the quad's
+    // own tokens; then neighbouring quads (lane ^ 4) trade accumulators, so that
+    // every lane now holds its neighbour's sums for the piece it takes in pass 1
+    // (pb of an even quad = pa of the odd quad next to it, and vice versa), and
+    // pass 1 adds the own tokens' share of that piece on top.
+    f32x4_t acc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    KVR_DISPATCH_NK(n_k, (v_pass<NK>(s_sk, info, W, pa * 16, turn, acc)))
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[c][g] = xchg4(acc[c][g]);
+    KVR_DISPATCH_NK(n_k, (v_pass<NK>(s_sk, info, W, pb * 16, turn + 1, acc)))
+    KVR_STAMP(8 + 2 * cc);
+    lds_barrier();                         // every wave is done with this V chunk
+    if (cc + 1 < NPH) stage_issue<NC, ROWB>(svg, s_sk, n_pieces, cc + 1, tid);
+
+    // Reduction over the workgroup's tokens.  Lane (quad, sub) holds, per head,
+    // the 8 channels of piece pb summed over the tokens of its quad and of the
+    // neighbouring quad; lanes l and l + 8 of a 16-lane row hold the same piece
+    // (one DPP rotation adds them), and the NROW rows meet in LDS.
+    if constexpr (true) {
+      float o[G][8];
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[g][c] = dpp_add<0x128>(acc[c][g]);
+      if ((lane & 15) < 8) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float* dst = s_part + (prow * G + g) * CH + pb * 8;
+          *reinterpret_cast<float4*>(dst) = make_float4(o[g][0], o[g][1], o[g][2], o[g][3]);
+          *reinterpret_cast<float4*>(dst + 4) = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
+        }
+      }
+    }
+    lds_barrier();
+    for (int idx = tid; idx < G * CH; idx += ST_THREADS) {
+      float v = 0.f;
+#pragma unroll
+      for (int pr = 0; pr < NROW; ++pr) v += s_part[pr * G * CH + idx];
+      a.part_o[part * G * D + (idx / CH) * D + cc * CH + (idx % CH)] = v;
+    }
+    // the next iteration's barrier (after its stage_wait) orders these reads
+    // before the next writes into s_part
+  }
+  KVR_STAMP(11);
+}
+
+#ifdef KVR_PHASE_TIMING
+extern "C" int kvr_debug_phase_times(unsigned long long* host_out, int n_words) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_phase_t), (size_t)n_words * 8, 0, hipMemcpyDeviceToHost);
+}
+#endif
+
+template <int G>
+static hipError_t launch64(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
+  static bool attr_set = false;
+  auto kern = attend_vague_staged64_kernel<G>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int units = d.B * d.Hkv;
+  const int units_pad = (units + 7) / 8 * 8;
+  hipLaunchKernelGGL(kern, dim3(units_pad * plan.n_vslices), dim3(ST_THREADS), plan.lds_bytes, st, d, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attend_vague_staged64(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
+                                        hipStream_t st) {
+  if (d.r != 3 || plan.ch != 64) return hipErrorInvalidValue;
+  // LDS: chunk + [32][G][64] floats + statistics + q; the plan reserves at least that
+  const size_t need = (((size_t)3 * d.w * 128 + 1023) & ~(size_t)1023) + (size_t)32 * d.G * 64 * 4 +
+                      (size_t)2 * 32 * d.G * 4 + (size_t)d.G * 256;
+  if (need > (size_t)plan.lds_bytes) return hipErrorInvalidValue;
+  switch (d.G) {
+    case 1: return launch64<1>(d, a, plan, st);
+    case 2: return launch64<2>(d, a, plan, st);
+    case 4: return launch64<4>(d, a, plan, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace kvr

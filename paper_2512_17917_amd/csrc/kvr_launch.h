@@ -75,6 +75,9 @@ hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, const
 // Staged kernel over the Vague list (bf16, values signed only, G <= 4, r in {3,4}).
 hipError_t launch_attend_vague_staged(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
                                       hipStream_t st);
+// Its specialisation for r = 3 and plan.ch = 64 (launch_attend_vague_staged forwards to it).
+hipError_t launch_attend_vague_staged64(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
+                                        hipStream_t st);
 
 hipError_t launch_select(const DevDesc& d, const float* scores, long long n_cap, int32_t* ret_pos,
                          int ret_cap, const int32_t* n_ctx, int n_recent, int k_candidate,
