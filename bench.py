@@ -2,13 +2,15 @@
 """Benchmark of the KVReviver decode hot path on one MI355X.
 
 A "step" is one decode step of the whole path for every layer of the workload:
-per layer  kvr_append -> kvr_select -> kvr_encode -> kvr_attend_decode  on all
-(sequence, kv head) units, layers one after another on one stream.  Inputs are
-synthetic (kvr_synth) and resident in HBM before the timed region.
+per layer  append -> select -> encode (one kvr_step_update launch) ->
+kvr_attend_decode  on all (sequence, kv head) units, layers one after another
+on one stream.  Inputs are synthetic (kvr_synth) and resident in HBM before the
+timed region.
 
 Prints ONE JSON line: decode steps/s, achieved algorithmic HBM bandwidth, the
-roofline object of the dominant kernel (main attention kernel, timed live with
-HIP events on the launch stream) and the CPU oracle timed on a bounded sample.
+roofline object of the dominant kernels (the token-touching attention kernels
+of a layer, timed live with HIP events on the launch stream) and the CPU oracle
+timed on a bounded sample.
 
     python bench.py [--workload c4] [--steps K] [--warmup W] [--gpus 1]
 """
@@ -27,6 +29,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch of the attention pair from the profiler's FETCH_SIZE / WRITE_SIZE counters (scaled by
+# what the same counters read for a kernel of known size); measured off-line, see
+# profiles/attend_pair_c4_hbm_traffic.txt.  Only for the workload it was measured on.
+MEASURED_TRAFFIC_BYTES = {"c4": 341706 * 1024}
 
 
 def algorithmic_bytes_per_unit(wl, n_ctx):
@@ -250,14 +257,15 @@ def main():
         "prompt_compress_ms_total": t_compress_ms,
         "roofline": {
             "kernel": "attention over retained + reconstructed tokens of one layer, all units: "
-                      "attend_retained_kernel and attend_vague_staged_kernel, launched side by side on two "
-                      "streams (first start to last end)",
+                      "attend_retained_kernel and attend_vague_staged64_kernel, launched side by side on two "
+                      "streams (HIP events on the caller's stream: before the fork, after the join)",
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if L == wl.layers else None,
+            "traffic_unit": "bytes per launch (profiles/attend_pair_c4_hbm_traffic.txt)",
             "algorithmic_bytes_per_launch": bytes_launch,
             "avg_launch_ms": avg_kern_s * 1e3,
             "launches_timed": len(kern_ms),

@@ -178,7 +178,8 @@ __device__ __forceinline__ void k_pass(const unsigned char* s_sk, const uint2 (&
   load_rows3(buf[0], s_sk, rb, co[0]);
   load_rows3(buf[1], s_sk, rb, co[1]);
   load_rows3(buf[2], s_sk, rb, co[2]);
-  uint4 m_cur = median3(buf[0]);
+  uint4 m[2];                            // medians of step t in m[t % 2]
+  m[0] = median3(buf[0]);
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
     int rn[3] = {0, 0, 0};
@@ -191,17 +192,16 @@ __device__ __forceinline__ void k_pass(const unsigned char* s_sk, const uint2 (&
       if (j < 5) load_rows3(buf[(t + 3) % 3], s_sk, rb, co[j + 3]);
       else if (k + 1 < NK) load_rows3(buf[(t + 3) % 3], s_sk, rn, co[j - 5]);
       KVR_PIN();
-      uint4 m_next = m_cur;
-      if (j < 7 || k + 1 < NK) m_next = median3(buf[(t + 1) % 3]);
+      if (j < 7 || k + 1 < NK) m[(t + 1) & 1] = median3(buf[(t + 1) % 3]);
       KVR_PIN();
-      const short4_t b_lo = pack_k4(m_cur.x, m_cur.y), b_hi = pack_k4(m_cur.z, m_cur.w);
+      const uint4 mc = m[t & 1];
+      const short4_t b_lo = pack_k4(mc.x, mc.y), b_hi = pack_k4(mc.z, mc.w);
       const uint4 qa = qx[j], qb = qx[(j + 1) & 7];
       ax = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pack_k4(qa.x, qa.y), b_lo, ax, 0, 0, 0);
       ay = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pack_k4(qb.x, qb.y), b_lo, ay, 0, 0, 0);
       ax = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pack_k4(qa.z, qa.w), b_hi, ax, 0, 0, 0);
       ay = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(pack_k4(qb.z, qb.w), b_hi, ay, 0, 0, 0);
       KVR_PIN();
-      m_cur = m_next;
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) s[k][g] += second_pair ? ay[g] : ax[g];
