@@ -70,6 +70,16 @@ __device__ __forceinline__ float xchg4(float x) {
   return __int_as_float(r);
 }
 
+// Byte addresses (relative to base) of a token's three rows for the 128-byte
+// row pitch of this kernel, and the masks that flip rows 1 and 2 relative to row 0
+__device__ __forceinline__ void rec_offsets(uint2 rec, int base, int (&rb)[3]) {
+  rb[0] = (int)(rec.x & 0x1ff80u) + base;
+  rb[1] = (int)(__builtin_amdgcn_ubfe(rec.x, 17, 10) << 7) + base;
+  rb[2] = (int)(rec.y & 0x1ff80u) + base;
+}
+__device__ __forceinline__ uint32_t rec_flip1(uint2 rec) { return (uint32_t)((int)rec.x >> 31) & 0x80008000u; }
+__device__ __forceinline__ uint32_t rec_flip2(uint2 rec) { return (uint32_t)((int)rec.y >> 31) & 0x80008000u; }
+
 // V phases: the rows of one piece of token J of the quad, plus the masks that
 // flip rows 1 and 2 relative to row 0
 struct VItem {
@@ -81,10 +91,10 @@ template <int J>
 __device__ __forceinline__ void v_fetch(VItem& o, uint2 inf_own, const unsigned char* s_sk, int co) {
   const uint2 inf = make_uint2(quad_bcast<J>(inf_own.x), quad_bcast<J>(inf_own.y));
   int rb[3];
-  row_offsets<3>(inf, rb, 7);
-  o.fm1 = info_flipmask<1>(inf);
-  o.fm2 = info_flipmask<2>(inf);
-  load_rows3(o.rows, s_sk, rb, co);
+  rec_offsets(inf, co, rb);
+  o.fm1 = rec_flip1(inf);
+  o.fm2 = rec_flip2(inf);
+  load_rows3(o.rows, s_sk, rb, 0);
 }
 
 __device__ __forceinline__ uint4 v_median(const VItem& it) {
@@ -174,7 +184,7 @@ __device__ __forceinline__ void k_pass(const unsigned char* s_sk, const uint2 (&
   // step lies between the two.)
   Rows3 buf[3];                          // rows of step t live in buf[t % 3]
   int rb[3];
-  row_offsets<3>(opaque(info[0]), rb, 7);
+  rec_offsets(opaque(info[0]), 0, rb);
   load_rows3(buf[0], s_sk, rb, co[0]);
   load_rows3(buf[1], s_sk, rb, co[1]);
   load_rows3(buf[2], s_sk, rb, co[2]);
@@ -183,7 +193,7 @@ __device__ __forceinline__ void k_pass(const unsigned char* s_sk, const uint2 (&
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
     int rn[3] = {0, 0, 0};
-    if (k + 1 < NK) row_offsets<3>(opaque(info[k + 1]), rn, 7);
+    if (k + 1 < NK) rec_offsets(opaque(info[k + 1]), 0, rn);
     f32x4_t ax = {0.f, 0.f, 0.f, 0.f}, ay = {0.f, 0.f, 0.f, 0.f};
     take_turn(k + turn);
 #pragma unroll
@@ -340,11 +350,16 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
     const int J = Jv[k];
     uint2 pk = make_uint2(0u, 0u);
     if (J >= 0) {
-      uint32_t f[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-      for (int i = 0; i < R; ++i)
-        f[i] = (uint32_t)(i * w + bucket_of(d, i, J)) | (sign_neg(d, i, J) ? 0x8000u : 0u);
-      pk = make_uint2(f[0] | (f[1] << 16), f[2] | (f[3] << 16));
+      // token record (2 dwords), laid out so that every field is one or two
+      // instructions away from its use: LDS row indices (< 1024 here) sit at
+      // bit 7 (row 0: x[7..16], row 2: y[7..16]) or at bit 17 (row 1: x[17..26]),
+      // bit 31 of x / y says whether row 1 / row 2 has the other sign than row 0,
+      // bit 0 of x is the sign of row 0 itself
+      const uint32_t r0 = (uint32_t)bucket_of(d, 0, J), r1 = (uint32_t)(w + bucket_of(d, 1, J)),
+                     r2 = (uint32_t)(2 * w + bucket_of(d, 2, J));
+      const uint32_t s0 = sign_neg(d, 0, J) ? 1u : 0u, s1 = sign_neg(d, 1, J) ? 1u : 0u,
+                     s2 = sign_neg(d, 2, J) ? 1u : 0u;
+      pk = make_uint2((r0 << 7) | (r1 << 17) | ((s1 ^ s0) << 31) | s0, (r2 << 7) | ((s2 ^ s0) << 31));
       vmask |= 1u << k;
     }
     info[k] = pk;
@@ -465,7 +480,7 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
   uint32_t W[KMAX][4];
 #pragma unroll
   for (int k = 0; k < KMAX; ++k) {
-    const uint32_t sgn = (info[k].x << 16) & 0x80000000u;
+    const uint32_t sgn = info[k].x << 31;
     float pf[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) pf[g] = __uint_as_float(__float_as_uint(s[k][g]) ^ sgn);
@@ -579,7 +594,7 @@ static hipError_t launch64(const DevDesc& d, const AttendArgs& a, const AttendPl
 
 hipError_t launch_attend_vague_staged64(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
                                         hipStream_t st) {
-  if (d.r != 3 || plan.ch != 64) return hipErrorInvalidValue;
+  if (d.r != 3 || plan.ch != 64 || 3 * d.w > 1024) return hipErrorInvalidValue;   // 10-bit LDS row indices
   // LDS: chunk + [32][G][64] floats + statistics + q; the plan reserves at least that
   const size_t need = (((size_t)3 * d.w * 128 + 1023) & ~(size_t)1023) + (size_t)32 * d.G * 64 * 4 +
                       (size_t)2 * 32 * d.G * 4 + (size_t)d.G * 256;
