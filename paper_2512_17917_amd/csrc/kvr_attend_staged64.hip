@@ -137,6 +137,12 @@ __device__ __forceinline__ uint2 opaque(uint2 v) {
   asm volatile("" : "+v"(v.x), "+v"(v.y));
   return v;
 }
+// same for a wave-uniform integer: addresses built from it are formed where they
+// are needed instead of at the top of the kernel (where they would be spilled)
+__device__ __forceinline__ int opaque_s(int v) {
+  asm volatile("" : "+s"(v));
+  return v;
+}
 
 // Nothing may be moved across this point by the instruction scheduler: keeps the
 // row reads of later pieces ahead of the arithmetic of the current one.
@@ -406,6 +412,8 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
 
   // ---- softmax weights against the workgroup's own maximum -------------------
   const int tot_cap = a.ret_cap + a.vague_cap;
+  const int unit_l = opaque_s(__builtin_amdgcn_readfirstlane(unit));
+  const int gw_l = opaque_s(__builtin_amdgcn_readfirstlane(gw));
   float mx[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) mx[g] = -__builtin_inff();
@@ -418,8 +426,8 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
       mx[g] = fmaxf(mx[g], s[k][g]);
     }
     if (a.logits != nullptr && valid) {
-      const int tok = (gw + k * NWT) * 64 + lane;
-      float* lg = a.logits + ((size_t)unit * tot_cap + a.ret_cap + tok) * G;
+      const int tok = (gw_l + k * NWT) * 64 + lane;
+      float* lg = a.logits + ((size_t)unit_l * tot_cap + a.ret_cap + tok) * G;
       if constexpr (G == 4) {
         *reinterpret_cast<float4*>(lg) = make_float4(s[k][0], s[k][1], s[k][2], s[k][3]);
       } else {
@@ -458,7 +466,7 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
     if ((lane & 15) == 0) s_stat[NROW * G + prow * G + g] = lsum[g];
   }
   lds_barrier();
-  const size_t part = (size_t)unit * a.n_slices + a.n_rslices + vs;
+  const size_t part = (size_t)unit_l * a.n_slices + a.n_rslices + opaque_s(__builtin_amdgcn_readfirstlane(vs));
   if (wave == 0) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
