@@ -150,6 +150,9 @@ __global__ __launch_bounds__(256) void attend_retained_kernel(DevDesc d, AttendA
   __shared__ float s_acc[NW][G][D];
   __shared__ float s_m[NW][G], s_l[NW][G];
 
+  // Same issue priority as the lower of the two levels that the staged kernel's
+  // waves alternate between: measured best when the two kernels share the CUs.
+  __builtin_amdgcn_s_setprio(1);
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int unit = item / n_rslices, slice = item % n_rslices;
     const int b = unit / d.Hkv, hk = unit % d.Hkv;
