@@ -73,60 +73,106 @@ __global__ __launch_bounds__(256) void encode_hash_kernel(
   if (out_sign) out_sign[(size_t)unit * cap + e] = (uint8_t)sg;
 }
 
-// One wave per (unit, row): stable counting sort of token ordinals by slot.
-__global__ __launch_bounds__(WAVE) void encode_sort_kernel(
+// One workgroup per (unit, row): stable counting sort of token ordinals by slot.
+// The list is cut into one contiguous segment per wave.
+//   1. every wave counts its segment's slots in a row of its own (LDS atomics:
+//      order does not matter for a count);
+//   2. per slot, the segment counts are turned into running offsets, the slot
+//      totals are scanned into start[], and row g of the table becomes the write
+//      cursor of slot s for segment g;
+//   3. every wave walks its segment 64 tokens at a time, in order: a token's
+//      place is its slot's cursor plus the number of lower lanes with the same
+//      slot, and the highest lane of each slot moves the cursor on.  Waves work
+//      on disjoint rows of the table and on disjoint ranges of the output, so
+//      there is no barrier inside the walk.
+// A slot's ordinals come out ascending, which fixes the summation order.
+constexpr int SORT_MAX_SEGS = 16;
+constexpr int SORT_LDS_INTS = 15360;       // 60 KB of table: segs * w + w <= this
+
+static int sort_segments(int w) {
+  int segs = (SORT_LDS_INTS - w) / w;
+  if (segs > SORT_MAX_SEGS) segs = SORT_MAX_SEGS;
+  if (segs < 1) segs = 1;
+  return segs;
+}
+
+__global__ __launch_bounds__(SORT_MAX_SEGS * WAVE) void encode_sort_kernel(
     DevDesc d, const int32_t* __restrict__ count, int cap, const int32_t* __restrict__ ws_bucket,
     int32_t* __restrict__ ws_order, int32_t* __restrict__ ws_start) {
-  __shared__ int cursor[ENC_BULK_MAX_W];
+  extern __shared__ int s_tab[];             // [segs][w] counts / cursors, then [w] totals / starts
+  const int w = d.w;
+  const int segs = blockDim.x / WAVE;
+  int* s_tot = s_tab + segs * w;
   const int ur = blockIdx.x;                 // unit * r + row
   const int unit = ur / d.r;
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
   const int cnt = clampi(count[unit], 0, cap);
   const int32_t* bk = ws_bucket + (size_t)ur * cap;
   int32_t* order = ws_order + (size_t)ur * cap;
-  int32_t* start = ws_start + (size_t)ur * (d.w + 1);
-  for (int s = lane; s < d.w; s += WAVE) cursor[s] = 0;
+  int32_t* start = ws_start + (size_t)ur * (w + 1);
+  // segment of this wave: whole 64-token chunks
+  const int chunks = (cnt + WAVE - 1) / WAVE;
+  const int per = (chunks + segs - 1) / segs;
+  const int lo = min(wave * per * WAVE, cnt), hi = min((wave + 1) * per * WAVE, cnt);
+  for (int i = tid; i < segs * w; i += blockDim.x) s_tab[i] = 0;
   __syncthreads();
-  for (int e = lane; e < cnt; e += WAVE) {
+  int* mine = s_tab + wave * w;
+  for (int e = lo + lane; e < hi; e += WAVE) {
     const int s = bk[e];
-    if (s >= 0) atomicAdd(&cursor[s], 1);
+    if (s >= 0) atomicAdd(&mine[s], 1);
   }
   __syncthreads();
-  int carry = 0;
-  for (int s0 = 0; s0 < d.w; s0 += WAVE) {
-    const int s = s0 + lane;
-    const int c = (s < d.w) ? cursor[s] : 0;
-    int incl = c;
-#pragma unroll
-    for (int off = 1; off < WAVE; off <<= 1) {
-      const int y = __shfl_up(incl, off);
-      if (lane >= off) incl += y;
+  for (int s = tid; s < w; s += blockDim.x) {
+    int run = 0;
+    for (int g = 0; g < segs; ++g) {
+      const int t = s_tab[g * w + s];
+      s_tab[g * w + s] = run;
+      run += t;
     }
-    const int excl = carry + incl - c;
-    if (s < d.w) { cursor[s] = excl; start[s] = excl; }
-    carry += __shfl(incl, WAVE - 1);
+    s_tot[s] = run;
   }
-  if (lane == 0) start[d.w] = carry;
   __syncthreads();
-  for (int e0 = 0; e0 < cnt; e0 += WAVE) {
+  if (wave == 0) {                            // exclusive scan of the slot totals
+    int carry = 0;
+    for (int s0 = 0; s0 < w; s0 += WAVE) {
+      const int s = s0 + lane;
+      const int c = (s < w) ? s_tot[s] : 0;
+      int incl = c;
+#pragma unroll
+      for (int off = 1; off < WAVE; off <<= 1) {
+        const int y = __shfl_up(incl, off);
+        if (lane >= off) incl += y;
+      }
+      if (s < w) { s_tot[s] = carry + incl - c; start[s] = carry + incl - c; }
+      carry += __shfl(incl, WAVE - 1);
+    }
+    if (lane == 0) start[w] = carry;
+  }
+  __syncthreads();
+  for (int s = tid; s < w; s += blockDim.x) {
+    const int st = s_tot[s];
+    for (int g = 0; g < segs; ++g) s_tab[g * w + s] += st;
+  }
+  __syncthreads();
+  volatile int* cur = mine;
+  for (int e0 = lo; e0 < hi; e0 += WAVE) {
     const int e = e0 + lane;
-    const int s = (e < cnt) ? bk[e] : -1;
+    const int s = (e < hi) ? bk[e] : -1;
     int lower = 0;
     bool higher = false;
+#pragma unroll 8
     for (int j = 0; j < WAVE; ++j) {
       const int sj = __shfl(s, j);
       const bool same = (sj == s);
       lower += (same && j < lane) ? 1 : 0;
       higher = higher || (same && j > lane);
     }
-    int base = 0;
-    if (s >= 0) base = cursor[s];
-    __syncthreads();
     if (s >= 0) {
-      order[base + lower] = e;
-      if (!higher) cursor[s] = base + lower + 1;
+      const int dst = cur[s] + lower;
+      order[dst] = e;
+      if (!higher) cur[s] = dst + 1;       // read above, written here by one lane per slot: same wave, program order
     }
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
@@ -200,8 +246,11 @@ static hipError_t launch_t(const DevDesc& d, const void* k_src, const void* v_sr
                      src_slot, tok_pos, count, cap, ws_bucket, out_bucket, out_sign);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(encode_sort_kernel, dim3(units * d.r), dim3(WAVE), 0, st, d, count, cap, ws_bucket,
-                     ws_order, ws_start);
+  {
+    const int segs = sort_segments(d.w);
+    hipLaunchKernelGGL(encode_sort_kernel, dim3(units * d.r), dim3(segs * WAVE),
+                       (size_t)(segs + 1) * d.w * sizeof(int), st, d, count, cap, ws_bucket, ws_order, ws_start);
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(encode_accum_kernel<T>, dim3((d.w + 3) / 4, d.r, units), dim3(256), 0, st, d,
