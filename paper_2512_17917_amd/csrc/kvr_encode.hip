@@ -176,6 +176,16 @@ __global__ __launch_bounds__(SORT_MAX_SEGS * WAVE) void encode_sort_kernel(
   }
 }
 
+// two neighbouring channels with one load
+__device__ __forceinline__ void load_pair(const float* p, float& a, float& b) {
+  const float2 v = *reinterpret_cast<const float2*>(p);
+  a = v.x; b = v.y;
+}
+__device__ __forceinline__ void load_pair(const bf16_t* p, float& a, float& b) {
+  const uint32_t v = *reinterpret_cast<const uint32_t*>(p);
+  a = __uint_as_float(v << 16); b = __uint_as_float(v & 0xffff0000u);
+}
+
 // One wave per (unit, row, slot): sequential float32 accumulation of the slot's
 // segment, lanes across channels (2 per lane).
 template <typename T>
@@ -198,21 +208,23 @@ __global__ __launch_bounds__(256) void encode_accum_kernel(
   const bool fk = (d.sign_mask & 1) != 0, fv = (d.sign_mask & 2) != 0;
   for (int p0 = lo; p0 < hi; p0 += WAVE) {
     // lanes fetch up to 64 list entries, then the wave walks them in order
-    int my_slot = -1, my_pos = 0;
+    int my_slot = 0;
+    bool my_neg = false;
     if (p0 + lane < hi) {
       const int e = order[p0 + lane];
       my_slot = src_slot[(size_t)unit * cap + e];
-      my_pos = tok_pos[(size_t)unit * cap + e];
+      my_neg = sign_neg(d, row, tok_pos[(size_t)unit * cap + e]);
     }
+    const unsigned long long negs = __ballot(my_neg);
     const int n = min(WAVE, hi - p0);
-#pragma unroll 4
+#pragma unroll 8
     for (int j = 0; j < n; ++j) {
       const int slot = __shfl(my_slot, j);
-      const int J = __shfl(my_pos, j);
-      const bool neg = sign_neg(d, row, J);
+      const bool neg = (negs >> j) & 1ull;
       const size_t src = ((size_t)unit * src_rows + slot) * D + 2 * lane;
-      const float k0 = Store<T>::load1(k_src + src), k1 = Store<T>::load1(k_src + src + 1);
-      const float v0 = Store<T>::load1(v_src + src), v1 = Store<T>::load1(v_src + src + 1);
+      float k0, k1, v0, v1;
+      load_pair(k_src + src, k0, k1);
+      load_pair(v_src + src, v0, v1);
       ak0 += (fk && neg) ? -k0 : k0;
       ak1 += (fk && neg) ? -k1 : k1;
       av0 += (fv && neg) ? -v0 : v0;
