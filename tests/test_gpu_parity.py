@@ -402,6 +402,39 @@ def test_attend_staged_channel_chunks(kvr):
     run_attend_case(kvr, rng, dtype, 3, 12, 3, 3, 50, 70, [4000, 3999, 1, 0, 64, 65, 2500, 4100, 128], 4100)
 
 
+def test_attend_staged64_shapes(kvr):
+    """bf16, r = 3, 64-channel chunks: the specialised staged kernel.  Group sizes 1, 2, 4; widths from a few
+    slots to the widest sketch that still fits LDS; 1 to 6 rounds of 64 tokens per wave; lists that end inside
+    a round, inside a quad and inside a pair; units with nothing in the list."""
+    rng = np.random.default_rng(56)
+    dtype = torch.bfloat16
+    for (G, w, nv, cap, ret) in [(1, 100, [300, 64, 1], 320, 40),
+                                 (2, 320, [1000, 999, 2], 1024, 70),        # widest: 3 * 320 rows of 128 B
+                                 (4, 7, [3070, 3071, 3072], 3072, 20),      # 6 rounds per wave, one workgroup
+                                 (4, 273, [130, 0, 67], 200, 130),          # few tokens: most waves idle
+                                 (2, 33, [5000, 4999, 63], 6000, 65)]:
+        say("attend staged64", G, w, nv)
+        B = len(nv)
+        run_attend_case(kvr, rng, dtype, B, G, 1, 3, w, ret, nv, cap)
+
+
+def test_attend_without_the_side_stream():
+    """KVR_NO_OVERLAP=1 (read once per process) runs the retained-slot and the staged kernel back to back on
+    the caller's stream: same results.  Runs two of the attend tests in a child process with the variable set."""
+    import os
+    import subprocess
+    import sys
+    if os.environ.get("KVR_NO_OVERLAP") == "1":
+        pytest.skip("already the child")
+    say("attend, side stream switched off (child process)")
+    env = dict(os.environ, KVR_NO_OVERLAP="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-q", "-x", "-m", "gpu", "tests/test_gpu_parity.py", "-k",
+                        "attend_staged64_shapes or attend_edges"], cwd=root, env=env, capture_output=True, text=True,
+                       timeout=600)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+
+
 def test_full_budget_matches_library_sdpa(kvr):
     """n_vague = 0 must be textbook softmax(qK^T/sqrt(d))V: checked against
     torch's SDPA on the CPU in float64 (not the oracle)."""
