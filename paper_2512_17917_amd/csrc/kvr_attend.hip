@@ -50,15 +50,18 @@ AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long
     }
     if (ch) {
       const long long wr = (vague_cap + 63) / 64;          // wave-rounds to cover the list
+      // Cost model: a workgroup that gives every wave rho rounds of 64 tokens takes
+      // about (2.8 + rho) round times (fixed part: staging four sketch chunks,
+      // hashes, softmax, reductions), and the launch runs ceil(workgroups / 256)
+      // such workgroups one after another on each CU.
       double best = 1e30;
       int best_rho = 1, best_n = 1;
       for (int rho = 1; rho <= STAGED_KMAX; ++rho) {
         const long long n = (wr + 8 * rho - 1) / (8 * rho);
-        const double util = (double)wr / (double)(n * 8 * rho);
-        const double wgs = (double)(units * n);
-        const double quant = (double)((units * n + 255) / 256) / (wgs / 256.0);
-        const double cost = ((rho + 1.0) / rho) / util * (wgs >= 256 ? quant : 1.0);
-        if (cost < best) { best = cost; best_rho = rho; best_n = (int)n; }
+        const long long rho_eff = (wr + 8 * n - 1) / (8 * n);      // rounds the busiest wave really gets
+        const long long waves_of_wgs = (units * n + 255) / 256;
+        const double cost = (double)waves_of_wgs * (2.8 + (double)rho_eff);
+        if (cost < best - 1e-9) { best = cost; best_rho = rho; best_n = (int)n; }
       }
       (void)best_rho;
       p.staged = true;
