@@ -28,7 +28,7 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 // value held by lane N of the caller's 16-lane row
 template <int N>
 __device__ __forceinline__ float row_bcast(float x) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + N, 0xf, 0xf, false));
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + N, 0xf, 0xf, true));
 }
 
 template <int G, int I>

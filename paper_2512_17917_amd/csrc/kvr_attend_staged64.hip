@@ -54,7 +54,7 @@ __device__ __forceinline__ uint4 median3(const Rows3& x) {
 // value of lane J of this lane's quad
 template <int J>
 __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {
-  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, J | (J << 2) | (J << 4) | (J << 6), 0xf, 0xf, false);
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, J | (J << 2) | (J << 4) | (J << 6), 0xf, 0xf, true);
 }
 template <int J>
 __device__ __forceinline__ float quad_bcast_f(float v) {

@@ -91,7 +91,7 @@ __device__ __forceinline__ void lds_barrier() {
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float x) {
-  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
 }
 // Sum over the lanes of a 16-lane row whose lane numbers are equal modulo LPT
 // (row rotations by LPT, 2 LPT, ..., 8); every lane ends up with its class's sum.
@@ -105,7 +105,7 @@ __device__ __forceinline__ float row_sum(float x) {
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_max(float x) {
-  return fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false)));
+  return fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true)));
 }
 // maximum over the 16 lanes of a row, in every lane
 __device__ __forceinline__ float row_max(float x) {
