@@ -226,6 +226,9 @@ def main():
     if not torch.isfinite(layers[-1].out).all():
         raise RuntimeError("non-finite attention output")
 
+    e_bytes = 4 if wl.dtype == "f32" else 2
+    prompt_bytes_layer = wl.units_per_layer * (2 * wl.n_vague0 * D * e_bytes + 2 * wl.sketch_slots * D * e_bytes
+                                               + 4 * wl.context)
     steps_per_s = K_steps / elapsed
     n_mid = wl.context + W + (K_steps + 1) // 2
     bytes_unit = algorithmic_bytes_per_unit(wl, n_mid)
@@ -255,6 +258,14 @@ def main():
         "algorithmic_bytes_per_step": bytes_step,
         "tokens_per_s": steps_per_s * B,
         "prompt_compress_ms_total": t_compress_ms,
+        # prompt compression (kvr_select over the whole prompt + bulk kvr_encode), once per layer, outside the
+        # timed steps; algorithmic bytes = evicted K and V rows read once + sketch written + scores read
+        "prompt_compress": {
+            "ms_per_layer": t_compress_ms / L,
+            "algorithmic_bytes_per_layer": prompt_bytes_layer,
+            "achieved_gbs": prompt_bytes_layer / (t_compress_ms / L * 1e-3) / 1e9,
+            "hbm_frac": prompt_bytes_layer / (t_compress_ms / L * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        },
         "roofline": {
             "kernel": "attention over retained + reconstructed tokens of one layer, all units: "
                       "attend_retained_kernel and attend_vague_staged64_kernel, launched side by side on two "
