@@ -266,7 +266,54 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
   __shared__ float sW[CMB_MAXW];
   const float* pml = a.part_ml + (size_t)unit * a.n_slices * G * 2;
   const bool w_in_lds = a.n_slices * G <= CMB_MAXW;
-  // global max and sum per head: wave w takes heads w, w + 4
+
+  // ---- score pass, first half: everything that does not depend on the global
+  //      statistics is requested before they are formed (token positions, the
+  //      spilled logits and the old scores), so that the two chains of memory
+  //      round trips (slice statistics -> reduction, position -> old score) run
+  //      side by side instead of one after the other.  Four tokens per thread. ----
+  constexpr int U = 4;
+  const bool do_scores = a.scores != nullptr;
+  const int tot_cap = a.ret_cap + a.vague_cap;
+  int total = 0;
+  int pos[U];
+  float x[U][G], old[U];
+  float* sc = do_scores ? a.scores + (size_t)unit * a.n_cap : nullptr;
+  const int t0 = blockIdx.x * 256 * U + tid;
+  if (do_scores) {
+    const int nv = a.n_vague ? clampi(a.n_vague[unit], 0, a.vague_cap) : 0;
+    total = a.ret_cap + nv;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * 256;
+      pos[u] = -1;
+      if (t < total) {
+        if (t < a.ret_cap) pos[u] = a.ret_pos ? a.ret_pos[(size_t)unit * a.ret_cap + t] : t;
+        else pos[u] = a.vague_pos[(size_t)unit * a.vague_cap + (t - a.ret_cap)];
+        if (pos[u] >= a.n_cap) pos[u] = -1;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * 256;
+#pragma unroll
+      for (int g = 0; g < G; ++g) x[u][g] = -__builtin_inff();
+      if (t < total) {
+        const float* lg = a.logits + ((size_t)unit * tot_cap + t) * G;
+        if constexpr (G == 4) {
+          const float4 v = *reinterpret_cast<const float4*>(lg);
+          x[u][0] = v.x; x[u][1] = v.y; x[u][2] = v.z; x[u][3] = v.w;
+        } else {
+#pragma unroll
+          for (int g = 0; g < G; ++g) x[u][g] = lg[g];
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) old[u] = (pos[u] >= 0) ? sc[pos[u]] : 0.f;
+  }
+
+  // ---- global max and sum per head: wave w takes heads w, w + 4 ----------------
   for (int g = wave; g < G; g += 4) {
     float M = -__builtin_inff(), L = 0.f;
     for (int s = lane; s < a.n_slices; s += WAVE) {
@@ -289,6 +336,42 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
     if (lane == 0) { sM[g] = M; sL[g] = L; }
   }
   __syncthreads();
+
+  // ---- score pass, second half ----------------------------------------------------
+  if (do_scores) {
+    float invL[G], M[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { M[g] = sM[g]; invL[g] = sL[g] > 0.f ? 1.f / sL[g] : 0.f; }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float acc = 0.f;
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+        if (x[u][g] != -__builtin_inff()) acc += __expf(x[u][g] - M[g]) * invL[g];
+      if (pos[u] >= 0) sc[pos[u]] = old[u] + acc;
+    }
+    // tokens beyond the launch width (the dispatch covers every token with one
+    // round; this loop only runs if a caller launches a narrower grid)
+    for (int base = (blockIdx.x + gridDim.x) * 256 * U; base < total; base += gridDim.x * 256 * U) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int t = base + tid + u * 256;
+        if (t >= total) continue;
+        int ps;
+        if (t < a.ret_cap) ps = a.ret_pos ? a.ret_pos[(size_t)unit * a.ret_cap + t] : t;
+        else ps = a.vague_pos[(size_t)unit * a.vague_cap + (t - a.ret_cap)];
+        if (ps < 0 || ps >= a.n_cap) continue;
+        const float* lg = a.logits + ((size_t)unit * tot_cap + t) * G;
+        float acc = 0.f;
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+          if (lg[g] != -__builtin_inff()) acc += __expf(lg[g] - M[g]) * invL[g];
+        sc[ps] += acc;
+      }
+    }
+  }
+
+  // ---- the unit's output: first workgroup of the unit ---------------------------
   if (blockIdx.x == 0) {
     if (w_in_lds) {
       for (int idx = tid; idx < a.n_slices * G; idx += 256) {
@@ -314,53 +397,6 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
         o = fmaf(po[(size_t)s * G * D + idx], wgt, o);
       }
       a.out[((size_t)b * d.Hq + (size_t)hk * G) * D + idx] = (L > 0.f) ? o / L : 0.f;
-    }
-  }
-  if (a.scores != nullptr) {
-    const int nv = a.n_vague ? clampi(a.n_vague[unit], 0, a.vague_cap) : 0;
-    const int tot_cap = a.ret_cap + a.vague_cap;
-    const int total = a.ret_cap + nv;
-    float invL[G], M[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) { M[g] = sM[g]; invL[g] = sL[g] > 0.f ? 1.f / sL[g] : 0.f; }
-    float* sc = a.scores + (size_t)unit * a.n_cap;
-    // four tokens per thread and round; the loads of a round are independent
-    constexpr int U = 4;
-    for (int t0 = blockIdx.x * 256 * U + tid; t0 < total; t0 += gridDim.x * 256 * U) {
-      int pos[U];
-      float p[U], old[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int t = t0 + u * 256;
-        pos[u] = -1;
-        if (t < total) {
-          if (t < a.ret_cap) pos[u] = a.ret_pos ? a.ret_pos[(size_t)unit * a.ret_cap + t] : t;
-          else pos[u] = a.vague_pos[(size_t)unit * a.vague_cap + (t - a.ret_cap)];
-          if (pos[u] >= a.n_cap) pos[u] = -1;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int t = min(t0 + u * 256, total - 1);
-        const float* lg = a.logits + ((size_t)unit * tot_cap + t) * G;
-        float x[G];
-        if constexpr (G == 4) {
-          const float4 v = *reinterpret_cast<const float4*>(lg);
-          x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
-        } else {
-#pragma unroll
-          for (int g = 0; g < G; ++g) x[g] = lg[g];
-        }
-        old[u] = (pos[u] >= 0) ? sc[pos[u]] : 0.f;
-        float acc = 0.f;
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-          if (x[g] != -__builtin_inff()) acc += __expf(x[g] - M[g]) * invL[g];
-        p[u] = acc;
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (pos[u] >= 0) sc[pos[u]] = old[u] + p[u];
     }
   }
 }

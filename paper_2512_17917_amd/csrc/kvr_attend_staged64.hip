@@ -71,36 +71,54 @@ __device__ __forceinline__ float xchg4(float x) {
 }
 
 // Byte addresses (relative to base) of a token's three rows for the 128-byte
-// row pitch of this kernel, and the masks that flip rows 1 and 2 relative to row 0
+// row pitch of this kernel, and the mask that flips the third listed row.
+// A median does not care about the order of its arguments, so the record lists
+// the rows in an order of its own: of the three signs g_0, g_1, g_2 at least two
+// agree; that majority sign is folded into the token's softmax weight, and the
+// row with the other sign (if there is one) is listed last, so that only one row
+// ever has to be flipped.
 __device__ __forceinline__ void rec_offsets(uint2 rec, int base, int (&rb)[3]) {
   rb[0] = (int)(rec.x & 0x1ff80u) + base;
   rb[1] = (int)(__builtin_amdgcn_ubfe(rec.x, 17, 10) << 7) + base;
   rb[2] = (int)(rec.y & 0x1ff80u) + base;
 }
-__device__ __forceinline__ uint32_t rec_flip1(uint2 rec) { return (uint32_t)((int)rec.x >> 31) & 0x80008000u; }
 __device__ __forceinline__ uint32_t rec_flip2(uint2 rec) { return (uint32_t)((int)rec.y >> 31) & 0x80008000u; }
 
-// V phases: the rows of one piece of token J of the quad, plus the masks that
-// flip rows 1 and 2 relative to row 0
+// V phases: the rows of one piece of token J of the quad, plus the mask that
+// flips the last row relative to the other two
 struct VItem {
   Rows3 rows;
-  uint32_t fm1, fm2;
+  uint32_t fm2;
 };
 
-template <int J>
-__device__ __forceinline__ void v_fetch(VItem& o, uint2 inf_own, const unsigned char* s_sk, int co) {
-  const uint2 inf = make_uint2(quad_bcast<J>(inf_own.x), quad_bcast<J>(inf_own.y));
+// What a lane derives from its own token's record for the V phases: the three
+// row offsets and the flip mask.  The other lanes of the quad fetch them with
+// quad broadcasts (DPP operands of the address additions and of the flips), so
+// a record is taken apart once per quad instead of once per lane.
+struct VOwn {
+  int o0, o1, o2;
+  uint32_t fm;
+};
+__device__ __forceinline__ VOwn v_own(uint2 rec) {
   int rb[3];
-  rec_offsets(inf, co, rb);
-  o.fm1 = rec_flip1(inf);
-  o.fm2 = rec_flip2(inf);
+  rec_offsets(rec, 0, rb);
+  return VOwn{rb[0], rb[1], rb[2], rec_flip2(rec)};
+}
+
+template <int J>
+__device__ __forceinline__ void v_fetch(VItem& o, const VOwn& own, const unsigned char* s_sk, int co) {
+  int rb[3];
+  rb[0] = (int)quad_bcast<J>((uint32_t)own.o0) + co;
+  rb[1] = (int)quad_bcast<J>((uint32_t)own.o1) + co;
+  rb[2] = (int)quad_bcast<J>((uint32_t)own.o2) + co;
+  o.fm2 = quad_bcast<J>(own.fm);
   load_rows3(o.rows, s_sk, rb, 0);
 }
 
 __device__ __forceinline__ uint4 v_median(const VItem& it) {
   Rows3 x;
   x.r0 = it.rows.r0;
-  x.r1 = xor4(it.rows.r1, it.fm1);
+  x.r1 = it.rows.r1;
   x.r2 = xor4(it.rows.r2, it.fm2);
   return median3(x);
 }
@@ -232,25 +250,27 @@ template <int NK>
 __device__ __forceinline__ void v_pass(const unsigned char* s_sk, const uint2 (&info)[ST_KMAX],
                                        const uint32_t (&W)[ST_KMAX][4], int co, int turn, f32x4_t (&acc)[8]) {
   VItem buf[4];
-  v_fetch<0>(buf[0], info[0], s_sk, co);
-  v_fetch<1>(buf[1], info[0], s_sk, co);
+  VOwn own = v_own(info[0]);
+  v_fetch<0>(buf[0], own, s_sk, co);
+  v_fetch<1>(buf[1], own, s_sk, co);
 #pragma unroll
   for (int k = 0; k < NK; ++k) {
     uint4 med[4];
     take_turn(k + turn);
-    v_fetch<2>(buf[2], info[k], s_sk, co);
+    v_fetch<2>(buf[2], own, s_sk, co);
     KVR_PIN();
     med[0] = v_median(buf[0]);
     KVR_PIN();
-    v_fetch<3>(buf[3], info[k], s_sk, co);
+    v_fetch<3>(buf[3], own, s_sk, co);
+    if (k + 1 < NK) own = v_own(info[k + 1]);
     KVR_PIN();
     med[1] = v_median(buf[1]);
     KVR_PIN();
-    if (k + 1 < NK) v_fetch<0>(buf[0], info[k + 1 < NK ? k + 1 : k], s_sk, co);
+    if (k + 1 < NK) v_fetch<0>(buf[0], own, s_sk, co);
     KVR_PIN();
     med[2] = v_median(buf[2]);
     KVR_PIN();
-    if (k + 1 < NK) v_fetch<1>(buf[1], info[k + 1 < NK ? k + 1 : k], s_sk, co);
+    if (k + 1 < NK) v_fetch<1>(buf[1], own, s_sk, co);
     KVR_PIN();
     med[3] = v_median(buf[3]);
     pv_piece(med, pack_k4(W[k][0], W[k][1]), pack_k4(W[k][2], W[k][3]), acc);
@@ -358,14 +378,22 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
     if (J >= 0) {
       // token record (2 dwords), laid out so that every field is one or two
       // instructions away from its use: LDS row indices (< 1024 here) sit at
-      // bit 7 (row 0: x[7..16], row 2: y[7..16]) or at bit 17 (row 1: x[17..26]),
-      // bit 31 of x / y says whether row 1 / row 2 has the other sign than row 0,
-      // bit 0 of x is the sign of row 0 itself
+      // bit 7 (first listed row: x[7..16], third: y[7..16]) or at bit 17 (second:
+      // x[17..26]); bit 0 of x is the majority sign of g_0, g_1, g_2 (1 = minus),
+      // bit 31 of y says whether the third listed row has the other sign.  The
+      // row whose sign differs from the other two, if any, is listed third.
       const uint32_t r0 = (uint32_t)bucket_of(d, 0, J), r1 = (uint32_t)(w + bucket_of(d, 1, J)),
                      r2 = (uint32_t)(2 * w + bucket_of(d, 2, J));
       const uint32_t s0 = sign_neg(d, 0, J) ? 1u : 0u, s1 = sign_neg(d, 1, J) ? 1u : 0u,
                      s2 = sign_neg(d, 2, J) ? 1u : 0u;
-      pk = make_uint2((r0 << 7) | (r1 << 17) | ((s1 ^ s0) << 31) | s0, (r2 << 7) | ((s2 ^ s0) << 31));
+      const uint32_t maj = (s0 & s1) | (s0 & s2) | (s1 & s2);
+      // the odd one out: row 0 if s0 != maj, else row 1 if s1 != maj, else row 2 (flipped or not)
+      const bool odd0 = s0 != maj, odd1 = s1 != maj;
+      const uint32_t ra = odd0 ? r2 : r0;                    // first listed
+      const uint32_t rbk = odd1 ? r2 : r1;                   // second listed
+      const uint32_t rc = odd0 ? r0 : (odd1 ? r1 : r2);      // third listed
+      const uint32_t flip = (s0 ^ s1) | (s0 ^ s2);           // 1 iff the signs are not all equal
+      pk = make_uint2((ra << 7) | (rbk << 17) | maj, (rc << 7) | (flip << 31));
       vmask |= 1u << k;
     }
     info[k] = pk;
@@ -419,6 +447,7 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
   for (int g = 0; g < G; ++g) mx[g] = -__builtin_inff();
 #pragma unroll
   for (int k = 0; k < KMAX; ++k) {
+    if (k >= n_k) break;                   // uniform over the wave: rounds it does not have cost nothing
     const bool valid = (vmask >> k) & 1u;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -455,6 +484,7 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
     lsum[g] = 0.f;
 #pragma unroll
     for (int k = 0; k < KMAX; ++k) {
+      if (k >= n_k) break;
       const float p = (s[k][g] == -__builtin_inff()) ? 0.f : __expf(s[k][g] - M[g]);
       s[k][g] = p;                 // from here on s holds the weights
       lsum[g] += p;
@@ -488,6 +518,8 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
   uint32_t W[KMAX][4];
 #pragma unroll
   for (int k = 0; k < KMAX; ++k) {
+    W[k][0] = W[k][1] = W[k][2] = W[k][3] = 0u;
+    if (k >= n_k) continue;
     const uint32_t sgn = info[k].x << 31;
     float pf[G];
 #pragma unroll
