@@ -3,7 +3,8 @@
 A plain, slow, deliberately unoptimised implementation of what the paper
 defines, one (layer, sequence, kv-head) unit at a time, written from the
 paper's Algorithm section (Vague Sketch: Algorithms 1 and 2; Recent and
-Candidate: Algorithms 3 and 4; Overview: accumulation of attention scores).
+Candidate: Algorithms 3 and 4, the swap loop of Algorithm 3 included; Overview:
+accumulation of attention scores).
 It shares no code with the HIP library and never imports it.  Only tests, the
 smoke check and the benchmark's CPU-baseline leg may import this file; the
 product path must never call it.
@@ -108,13 +109,15 @@ def sketch_zeros(r: int, w: int, D: int):
 
 
 def insert(SK, SV, params, tok_pos, K_tok, V_tok, *, storage="f64",
-           acc_dtype=np.float64, sign_mask=2):
+           acc_dtype=np.float64, sign_mask=2, coef=None):
     """V.Insert for a batch of tokens, in list order.
 
     For each token with index J and each row i:
         SK[i][h_i(J)] += key,   SV[i][h_i(J)] += value * g_i(J)
     Keys are not signed (sign_mask bit 0 clear) and values are (bit 1 set), as
     in Algorithm 1; the other settings of sign_mask exist for experiments.
+    coef (optional, +1 or -1 per listed token) turns an entry into V.Delete of
+    Algorithm 3's swap loop: the same slots, the contribution subtracted.
     Returns new (SK, SV); slots that receive nothing keep their content.
     """
     r, w, _ = SK.shape
@@ -123,6 +126,9 @@ def insert(SK, SV, params, tok_pos, K_tok, V_tok, *, storage="f64",
     acc_k, acc_v = {}, {}
     for n, J in enumerate(tok_pos):
         J = int(J)
+        cf = 1 if coef is None else int(coef[n])
+        if cf not in (1, -1):
+            raise ValueError("coef entries are +1 (insert) or -1 (delete)")
         for i in range(r):
             s = bucket_of(params[i], J, w)
             g = sign_of(params[i], J)
@@ -130,8 +136,8 @@ def insert(SK, SV, params, tok_pos, K_tok, V_tok, *, storage="f64",
             if key not in acc_k:
                 acc_k[key] = SK[i, s].astype(acc_dtype)
                 acc_v[key] = SV[i, s].astype(acc_dtype)
-            gk = g if (sign_mask & 1) else 1
-            gv = g if (sign_mask & 2) else 1
+            gk = cf * (g if (sign_mask & 1) else 1)
+            gv = cf * (g if (sign_mask & 2) else 1)
             acc_k[key] = acc_k[key] + acc_dtype(gk) * np.asarray(K_tok[n]).astype(acc_dtype)
             acc_v[key] = acc_v[key] + acc_dtype(gv) * np.asarray(V_tok[n]).astype(acc_dtype)
     for (i, s), v in acc_k.items():
@@ -200,6 +206,59 @@ def select(scores, ret_pos, n_ctx: int, n_recent: int, k_candidate: int):
     ev = [s for s in elig if s not in keep]
     return (np.array(ev, dtype=np.int64),
             np.array([ret_pos[s] for s in ev], dtype=np.int64))
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 3, swap loop: a Vague token that has become important enough
+# changes places with the least important Candidate token
+# ---------------------------------------------------------------------------
+def swap_pick(scores, ret_pos, vague_pos, n_ctx: int, n_recent: int, replace_rate):
+    """One evaluation of the loop condition
+        C.Min_Score() * ReplaceRate < V.Max_Score().
+    Candidate = retained tokens that are not Recent (position < n_ctx - n_recent).
+    C.Min: lowest cumulative score, ties: the later position (the order in which
+    `select` would pop them).  V.Max: highest cumulative score among the Vague
+    tokens, ties: the earlier position.  The product and the comparison are taken
+    in float32, the type the scores are kept in.  Returns (slot of the Candidate
+    minimum, index into vague_pos of the Vague maximum) or None when the condition
+    does not hold (or either part is empty)."""
+    recent_from = n_ctx - n_recent
+    cand = [s for s in range(len(ret_pos)) if 0 <= ret_pos[s] < recent_from]
+    if not cand or len(vague_pos) == 0:
+        return None
+    s_min = min(cand, key=lambda s: (float(scores[ret_pos[s]]), -int(ret_pos[s])))
+    i_max = min(range(len(vague_pos)),
+                key=lambda i: (-float(scores[vague_pos[i]]), int(vague_pos[i])))
+    lhs = np.float32(scores[ret_pos[s_min]]) * np.float32(replace_rate)
+    if not (np.float32(lhs) < np.float32(scores[vague_pos[i_max]])):
+        return None
+    return s_min, i_max
+
+
+def swap_once(SK, SV, params, K_ret, V_ret, ret_pos, vague_pos, s_min: int, i_max: int, *,
+              storage="f64", acc_dtype=np.float64, median_mode="midmean", sign_mask=2):
+    """The body of the swap loop for the chosen pair:
+        tmp <- V.Query(J);  V.Delete(tmp);  V.Insert(C.Top_Pop());  C.Push(tmp)
+    J = vague_pos[i_max]; the popped Candidate sits in retained slot s_min.
+    V.Delete subtracts the queried estimate tmp from exactly the slots that an
+    insert of J adds to (with the same signs); Delete and Insert form one sketch
+    update in that order (a slot that both touch is rounded to storage once).
+    The Candidate's slot then holds tmp at position J, and J's entry of the Vague
+    index list is overwritten with the popped token's position.
+    Returns new (SK, SV); K_ret, V_ret, ret_pos, vague_pos are modified in place."""
+    J = int(vague_pos[i_max])
+    pc = int(ret_pos[s_min])
+    k_hat, v_hat = query(SK, SV, params, [J], storage=storage, median_mode=median_mode,
+                         sign_mask=sign_mask)
+    SK, SV = insert(SK, SV, params, [J, pc],
+                    [k_hat[0], np.array(K_ret[s_min], copy=True)],
+                    [v_hat[0], np.array(V_ret[s_min], copy=True)],
+                    storage=storage, acc_dtype=acc_dtype, sign_mask=sign_mask, coef=[-1, 1])
+    K_ret[s_min] = k_hat[0]
+    V_ret[s_min] = v_hat[0]
+    ret_pos[s_min] = J
+    vague_pos[i_max] = pc
+    return SK, SV
 
 
 # ---------------------------------------------------------------------------
@@ -310,6 +369,23 @@ class UnitState:
             self.vague_pos.extend(int(p) for p in ev_pos)
         return ev_slots, ev_pos
 
+    def swap_back(self, replace_rate, max_swaps):
+        """The swap loop of Algorithm 3, at most max_swaps rounds.  Returns the
+        list of (Vague position brought back, Candidate position sent out)."""
+        done = []
+        for _ in range(max_swaps):
+            pick = swap_pick(self.scores, self.ret_pos, self.vague_pos, self.n_ctx,
+                             self.n_recent, replace_rate)
+            if pick is None:
+                break
+            s_min, i_max = pick
+            done.append((int(self.vague_pos[i_max]), int(self.ret_pos[s_min])))
+            self.SK, self.SV = swap_once(
+                self.SK, self.SV, self.params, self.K_ret, self.V_ret, self.ret_pos,
+                self.vague_pos, s_min, i_max, storage=self.storage, acc_dtype=self.acc_dtype,
+                median_mode=self.median_mode, sign_mask=self.sign_mask)
+        return done
+
     def attend(self, q, scale):
         out, self.scores, p = attend_decode(
             q, self.K_ret, self.V_ret, self.ret_pos, self.SK, self.SV, self.params,
@@ -317,10 +393,13 @@ class UnitState:
             median_mode=self.median_mode, sign_mask=self.sign_mask)
         return out, p
 
-    def decode_step(self, k_new, v_new, q, scale):
-        """append -> select -> insert -> rebuild + attend + accumulate scores."""
+    def decode_step(self, k_new, v_new, q, scale, *, replace_rate=None, max_swaps=0):
+        """append -> select -> insert -> (swap loop, if replace_rate is given) ->
+        rebuild + attend + accumulate scores."""
         self.append(k_new, v_new)
         ev = self.compress()
+        if replace_rate is not None and max_swaps > 0:
+            self.swap_back(replace_rate, max_swaps)
         out, p = self.attend(q, scale)
         return out, ev, p
 

@@ -530,3 +530,191 @@ def test_multi_step_bookkeeping_invariants():
     # the same order when nothing needs rounding (checked with exact data above);
     # here: it only ever holds bf16-representable values
     assert np.array_equal(st.SK, O.to_storage(st.SK, "bf16"))
+
+
+# ------------------------------------------------------------------ swap loop (Algorithm 3)
+def _injective_positions(params, r, w, n, rng, limit=4000):
+    """Positions whose slots are pairwise distinct in every row (no collisions)."""
+    chosen, used = [], [set() for _ in range(r)]
+    for J in rng.permutation(limit):
+        hs = [O.bucket_of(params[i], int(J), w) for i in range(r)]
+        if all(hs[i] not in used[i] for i in range(r)):
+            chosen.append(int(J))
+            for i in range(r):
+                used[i].add(hs[i])
+            if len(chosen) == n:
+                return chosen
+    raise AssertionError("no injective set found")
+
+
+def test_swap_pick_against_brute_force_and_boundaries():
+    rng = np.random.default_rng(21)
+    for trial in range(200):
+        n_ret, n_vague, n_ctx, n_recent = 9, 7, 40, 5
+        pos = rng.permutation(n_ctx)
+        ret_pos = np.full(n_ret + 2, -1, dtype=np.int64)
+        recent = np.arange(n_ctx - n_recent, n_ctx)
+        others = np.array([p for p in pos if p < n_ctx - n_recent])
+        ret_pos[:n_recent] = recent
+        ret_pos[n_recent + 1:n_recent + 1 + 4] = others[:4]            # 4 candidates, with an empty slot between
+        vague = [int(p) for p in others[4:4 + n_vague]]
+        scores = rng.integers(0, 4, size=n_ctx).astype(np.float32)        # many ties
+        rate = float(rng.choice([1.0, 1.1, 1.5]))
+        got = O.swap_pick(scores, ret_pos, vague, n_ctx, n_recent, rate)
+        # brute force with explicit sorting
+        cand = [(float(scores[ret_pos[s]]), -int(ret_pos[s]), s) for s in range(len(ret_pos))
+                if 0 <= ret_pos[s] < n_ctx - n_recent]
+        cand.sort()
+        vg = sorted([(-float(scores[p]), p, i) for i, p in enumerate(vague)])
+        cmin, vmax = cand[0], vg[0]
+        cond = np.float32(np.float32(cmin[0]) * np.float32(rate)) < np.float32(-vmax[0])
+        if cond:
+            assert got == (cmin[2], vmax[2])
+        else:
+            assert got is None
+    # strict inequality: equal scores at rate 1.0 do not swap; a Recent token is never the minimum
+    scores = np.ones(10, dtype=np.float32)
+    ret_pos = np.array([0, 1, 8, 9], dtype=np.int64)
+    assert O.swap_pick(scores, ret_pos, [2, 3], 10, 2, 1.0) is None
+    scores[3] = 2.0
+    assert O.swap_pick(scores, ret_pos, [2, 3], 10, 2, 1.0) == (1, 1)          # tie of candidates 0, 1: later position
+    scores[8] = 0.0                                                             # recent token with the lowest score: ignored
+    assert O.swap_pick(scores, ret_pos, [2, 3], 10, 2, 1.0) == (1, 1)
+    assert O.swap_pick(scores, ret_pos, [], 10, 2, 1.0) is None
+    assert O.swap_pick(scores, np.array([8, 9]), [2, 3], 10, 2, 1.0) is None
+    # the product is taken in float32: 1.1f * 10f = 11.000000238..., which rounds to 11.0f, so a
+    # Vague score of 11 does not exceed it
+    scores = np.array([10.0, 11.0, 0, 0], dtype=np.float32)
+    assert O.swap_pick(scores, np.array([0, 2, 3]), [1], 4, 2, 1.1) is None
+    assert O.swap_pick(scores, np.array([0, 2, 3]), [1], 4, 2, 1.09) == (0, 0)
+
+
+def test_swap_restores_token_exactly_without_collisions():
+    """With no collisions V.Query returns the token itself, so V.Delete removes it
+    without a trace: after the swap the sketch equals a sketch built from scratch
+    from the new Vague set, and the Candidate slot holds the original token."""
+    rng = np.random.default_rng(22)
+    r, w, D = 3, 64, 128
+    params = rand_params(rng, r)
+    pos = _injective_positions(params, r, w, 12, rng)
+    vague, cand = pos[:10], pos[10:]
+    K = {p: rng.integers(-8, 9, size=D).astype(np.float64) for p in pos}
+    V = {p: rng.integers(-8, 9, size=D).astype(np.float64) for p in pos}
+    SK, SV = O.sketch_zeros(r, w, D)
+    SK, SV = O.insert(SK, SV, params, vague, [K[p] for p in vague], [V[p] for p in vague])
+    K_ret = np.stack([K[p] for p in cand]); V_ret = np.stack([V[p] for p in cand])
+    ret_pos = np.array(cand, dtype=np.int64)
+    vp = list(vague)
+    J, pc = vp[3], cand[1]
+    SK2, SV2 = O.swap_once(SK, SV, params, K_ret, V_ret, ret_pos, vp, 1, 3)
+    new_vague = [p for p in vague if p != J] + [pc]
+    SKr, SVr = O.sketch_zeros(r, w, D)
+    SKr, SVr = O.insert(SKr, SVr, params, new_vague, [K[p] for p in new_vague], [V[p] for p in new_vague])
+    assert np.array_equal(SK2, SKr) and np.array_equal(SV2, SVr)
+    assert np.array_equal(K_ret[1], K[J]) and np.array_equal(V_ret[1], V[J])
+    assert ret_pos[1] == J and vp[3] == pc and sorted(vp) == sorted(new_vague)
+    # every token of the new Vague set is still recovered exactly
+    kq, vq = O.query(SK2, SV2, params, vp)
+    assert np.array_equal(kq, np.stack([K[p] for p in vp])) and np.array_equal(vq, np.stack([V[p] for p in vp]))
+
+
+def test_swap_with_collisions_against_onehot_formulation():
+    """Delete = subtract the queried estimate from the slots an insert of J adds
+    to, with the same signs (dense one-hot formulation, exact integer data)."""
+    rng = np.random.default_rng(23)
+    r, w, D = 3, 3, 128
+    params = rand_params(rng, r)
+    vague = [int(p) for p in rng.permutation(60)[:20]]
+    cand_pos, cand_slot = 77, 2
+    Kt = rng.integers(-4, 5, size=(20, D)).astype(np.float64)
+    Vt = rng.integers(-4, 5, size=(20, D)).astype(np.float64)
+    SK, SV = O.sketch_zeros(r, w, D)
+    SK, SV = O.insert(SK, SV, params, vague, Kt, Vt)
+    K_ret = rng.integers(-4, 5, size=(4, D)).astype(np.float64)
+    V_ret = rng.integers(-4, 5, size=(4, D)).astype(np.float64)
+    kc, vc = K_ret[cand_slot].copy(), V_ret[cand_slot].copy()
+    ret_pos = np.array([70, 71, cand_pos, 90], dtype=np.int64)
+    i_max = 5
+    J = vague[i_max]
+
+    def onehot(Jx):
+        H = np.zeros((r, w)); g = np.zeros(r)
+        for i in range(r):
+            a, b, c, d = params[i]
+            H[i, (((a * Jx + b) % (1 << 64)) >> 32) * w >> 32] = 1.0
+            g[i] = -1.0 if ((c * Jx + d) % (1 << 64)) >= (1 << 63) else 1.0
+        return H, g
+    HJ, gJ = onehot(J)
+    Hc, gc = onehot(cand_pos)
+    k_hat = np.median(np.stack([HJ[i] @ SK[i] for i in range(r)]), axis=0)
+    v_hat = np.median(np.stack([gJ[i] * (HJ[i] @ SV[i]) for i in range(r)]), axis=0)
+    SK_ref = SK - HJ[:, :, None] * k_hat[None, None, :] + Hc[:, :, None] * kc[None, None, :]
+    SV_ref = SV - (gJ[:, None] * HJ)[:, :, None] * v_hat[None, None, :] + (gc[:, None] * Hc)[:, :, None] * vc[None, None, :]
+    vp = list(vague)
+    SK2, SV2 = O.swap_once(SK, SV, params, K_ret, V_ret, ret_pos, vp, cand_slot, i_max)
+    assert np.array_equal(SK2, SK_ref) and np.array_equal(SV2, SV_ref)
+    assert np.array_equal(K_ret[cand_slot], k_hat) and np.array_equal(V_ret[cand_slot], v_hat)
+    assert ret_pos[cand_slot] == J and vp[i_max] == cand_pos
+    # the total key mass of every row changes by exactly (candidate - estimate)
+    for i in range(r):
+        assert np.array_equal(SK2[i].sum(axis=0) - SK[i].sum(axis=0), kc - k_hat)
+
+
+def test_swap_rounds_shared_slot_once_delete_then_insert():
+    """Delete and insert of one swap are one sketch update: a slot both touch is
+    old - estimate + candidate in float32 in that order, rounded to bf16 once."""
+    r, w, D = 1, 1, 128                       # one slot: everything collides
+    params = [(1, 0, 1, 0)]                   # g = +1 for small J
+    SK = np.full((1, 1, D), 256.0); SV = np.full((1, 1, D), 256.0)
+    K_ret = np.full((1, D), 1.0); V_ret = np.full((1, D), 1.0)      # candidate adds 1 (half an ulp at 256 in bf16)
+    ret_pos = np.array([5], dtype=np.int64)
+    vp = [3]
+    SK2, SV2 = O.swap_once(SK, SV, params, K_ret, V_ret, ret_pos, vp, 0, 0, storage="bf16",
+                           acc_dtype=np.float32)
+    # estimate = the slot itself (256): 256 - 256 + 1 = 1 exactly; rounding twice (256 - 256 -> 0, 0 + 1) agrees,
+    # but insert-then-delete with a rounding in between (256 + 1 -> 256, - 256 -> 0) would not
+    assert np.all(SK2 == 1.0) and np.all(SV2 == 1.0)
+    assert np.all(K_ret == 256.0) and ret_pos[0] == 3 and vp == [5]
+    # the order inside the float32 sum: (2^24 - 2^24) + 1 = 1, whereas (2^24 + 1) - 2^24 = 0 in float32
+    SK = np.full((1, 1, D), 2.0 ** 24); SV = np.full((1, 1, D), 2.0 ** 24)
+    K_ret = np.full((1, D), 1.0); V_ret = np.full((1, D), 1.0)
+    SK2, SV2 = O.swap_once(SK, SV, params, K_ret, V_ret, np.array([5]), [3], 0, 0, storage="f32",
+                           acc_dtype=np.float32)
+    assert np.all(SK2 == 1.0) and np.all(SV2 == 1.0)
+
+
+def test_swap_loop_exit_condition_and_partition():
+    rng = np.random.default_rng(24)
+    N, D, r, w = 48, 128, 3, 4
+    params = O.hash_params_from_seed(5, r)
+    K = O.to_storage(rng.standard_normal((N + 4, D)), "bf16")
+    V = O.to_storage(rng.standard_normal((N + 4, D)), "bf16")
+    q = O.to_storage(rng.standard_normal((5, 2, D)), "bf16")
+    scale = 1 / math.sqrt(D)
+    st = O.dense_prefill_state(K[:N], V[:N], q[0], scale, r, w, params, "bf16",
+                               n_recent=6, k_candidate=8, n_cap=N + 4, acc_dtype=np.float32)
+    st.compress()
+    st = O.compact(st, 15)
+    total_swaps = 0
+    for t in range(4):
+        n_vague_before = len(st.vague_pos) + 1
+        st.decode_step(K[N + t], V[N + t], q[t + 1], scale, replace_rate=1.1, max_swaps=64)
+        assert len(st.vague_pos) == n_vague_before                  # swaps keep both parts' sizes
+        assert (st.ret_pos >= 0).sum() == 14
+        allpos = sorted(st.vague_pos + [int(p) for p in st.ret_pos if p >= 0])
+        assert allpos == list(range(st.n_ctx))                       # still a partition of the context
+        # after one more unbounded loop nothing is left to swap, and the exit condition holds
+        done = st.swap_back(1.1, 1000)
+        total_swaps += len(done)
+        assert O.swap_pick(st.scores, st.ret_pos, st.vague_pos, st.n_ctx, st.n_recent, 1.1) is None
+        cand = [p for p in st.ret_pos if 0 <= p < st.n_ctx - st.n_recent]
+        cmin = min(float(st.scores[p]) for p in cand)
+        vmax = max(float(st.scores[p]) for p in st.vague_pos)
+        assert not (np.float32(np.float32(cmin) * np.float32(1.1)) < np.float32(vmax))
+    # max_swaps bounds the loop
+    st2 = O.dense_prefill_state(K[:N], V[:N], q[0], scale, r, w, params, "bf16",
+                                n_recent=6, k_candidate=8, n_cap=N + 4, acc_dtype=np.float32)
+    st2.compress()
+    st2.scores[st2.vague_pos] += 10.0          # every Vague token now outranks every Candidate
+    assert len(st2.swap_back(1.1, 3)) == 3
+    assert len(st2.swap_back(1.1, 0)) == 0
