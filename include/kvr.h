@@ -217,6 +217,44 @@ int32_t kvr_step_update(const kvr_desc* desc, const void* k_new, const void* v_n
                         void* sketch_k, void* sketch_v, void* stream);
 
 /*
+ * The swap loop of Algorithm 3 ("Additionally, we set a swap mechanism, allowing
+ * tokens in the Vague Part to be swapped back to the Candidate Part"), per unit,
+ * at most max_swaps times:
+ *     while C.Min_Score() * ReplaceRate < V.Max_Score():
+ *         tmp <- V.Query(V.Max_Score_Index());  V.Delete(tmp)
+ *         V.Insert(C.Top_Pop());  C.Push(tmp)
+ * Candidate = occupied slots with ret_pos < n_ctx[b] - n_recent.  C.Min: lowest
+ * scores[ret_pos], ties: the later position (the token kvr_select would pop
+ * first).  V.Max: highest scores[vague_pos[i]], ties: the earlier position.  The
+ * product and the comparison are float32.  V.Query is Algorithm 2 (as in
+ * kvr_reconstruct).  V.Delete subtracts the queried estimate from the slots an
+ * insert of that position adds to, with the same signs; together with the insert
+ * of the popped Candidate it is one sketch update in the sense of kvr_encode
+ * (list order: delete, insert; float32 sums; a touched slot is rounded once).
+ * Afterwards the Candidate's slot holds the estimate (k_ret, v_ret) at the Vague
+ * token's position (ret_pos), and the Vague token's entry of vague_pos holds the
+ * popped Candidate's position; n_vague and the number of occupied slots do not
+ * change.  The paper fixes ReplaceRate = 1.1 (ablation of the replacement rate).
+ *   scores     dev float32 [B, Hkv, n_cap], read
+ *   k_ret, v_ret  dev [B, Hkv, ret_cap, D] storage type, read and written
+ *   ret_pos    dev int32 [B, Hkv, ret_cap], read and written;  n_ctx dev int32 [B]
+ *   sketch_k, sketch_v  dev [B, Hkv, r, w, D], read and written
+ *   vague_pos  dev int32 [B, Hkv, vague_cap], read and written; n_vague dev int32
+ *              [B, Hkv], read (clamped to [0, vague_cap])
+ *   n_swapped  dev int32 [B, Hkv] or NULL: swaps done
+ *   swap_log   dev int32 [B, Hkv, max_swaps, 2] or NULL: per swap (position brought
+ *              back from the Vague part, position sent there)
+ * replace_rate must be finite and > 0, 0 <= max_swaps <= 65536, else
+ * KVR_ERR_INVALID_ARG.  max_swaps = 0 only writes n_swapped = 0.
+ */
+int32_t kvr_swap_back(const kvr_desc* desc, const float* scores, int64_t n_cap,
+                      void* k_ret, void* v_ret, int32_t* ret_pos, int32_t ret_cap,
+                      const int32_t* n_ctx, int32_t n_recent, float replace_rate, int32_t max_swaps,
+                      void* sketch_k, void* sketch_v,
+                      int32_t* vague_pos, const int32_t* n_vague, int32_t vague_cap,
+                      int32_t* n_swapped, int32_t* swap_log, void* stream);
+
+/*
  * Algorithm 2, batched: for token position J = tok_pos[u, e], e < count[u],
  *     k_out[u, e, c] = median_i sketch_k[u, i, h_i(J), c]
  *     v_out[u, e, c] = median_i g_i(J) * sketch_v[u, i, h_i(J), c]

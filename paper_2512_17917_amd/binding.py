@@ -31,7 +31,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvr.so")
 
 EXPORTS = ["kvr_version", "kvr_last_hip_error", "kvr_profile_events", "kvr_hash_params_from_seed", "kvr_hash_host",
            "kvr_workspace_size", "kvr_append", "kvr_select", "kvr_encode", "kvr_step_update",
-           "kvr_reconstruct", "kvr_attend_decode"]
+           "kvr_swap_back", "kvr_reconstruct", "kvr_attend_decode"]
 
 
 class KvrError(RuntimeError):
@@ -83,6 +83,9 @@ def lib() -> C.CDLL:
         L.kvr_step_update.restype = i32
         L.kvr_step_update.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, i64, i32, i32, vp, vp, vp, i32,
                                       vp, vp, i32, vp, vp, vp]
+        L.kvr_swap_back.restype = i32
+        L.kvr_swap_back.argtypes = [dp, vp, i64, vp, vp, vp, i32, vp, i32, C.c_float, i32, vp, vp, vp, vp, i32,
+                                    vp, vp, vp]
         L.kvr_reconstruct.restype = i32
         L.kvr_reconstruct.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp]
         L.kvr_attend_decode.restype = i32
@@ -252,6 +255,22 @@ def kvr_step_update(desc, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap, s
         _ptr(n_vague, torch.int32, U, "n_vague", True), vague_cap,
         _ptr(sketch_k, dt, U * S, "sketch_k"), _ptr(sketch_v, dt, U * S, "sketch_v"), _stream())
     _check("kvr_step_update", rc)
+
+
+def kvr_swap_back(desc, scores, n_cap, k_ret, v_ret, ret_pos, ret_cap, n_ctx, n_recent, replace_rate,
+                  max_swaps, sketch_k, sketch_v, vague_pos, n_vague, vague_cap, n_swapped=None, swap_log=None):
+    U, D, dt = desc.batch * desc.n_kv_heads, desc.head_dim, _torch_dtype(desc)
+    S = desc.r * desc.w * D
+    rc = lib().kvr_swap_back(
+        C.byref(desc), _ptr(scores, torch.float32, U * n_cap, "scores"), n_cap,
+        _ptr(k_ret, dt, U * ret_cap * D, "k_ret"), _ptr(v_ret, dt, U * ret_cap * D, "v_ret"),
+        _ptr(ret_pos, torch.int32, U * ret_cap, "ret_pos"), ret_cap,
+        _ptr(n_ctx, torch.int32, desc.batch, "n_ctx"), n_recent, C.c_float(replace_rate), max_swaps,
+        _ptr(sketch_k, dt, U * S, "sketch_k"), _ptr(sketch_v, dt, U * S, "sketch_v"),
+        _ptr(vague_pos, torch.int32, U * vague_cap, "vague_pos"), _ptr(n_vague, torch.int32, U, "n_vague"),
+        vague_cap, _ptr(n_swapped, torch.int32, U, "n_swapped", True),
+        _ptr(swap_log, torch.int32, U * max(max_swaps, 1) * 2, "swap_log", True), _stream())
+    _check("kvr_swap_back", rc)
 
 
 def kvr_reconstruct(desc, sketch_k, sketch_v, tok_pos, count, cap, k_out, v_out):

@@ -193,6 +193,28 @@ int32_t kvr_step_update(const kvr_desc* desc, const void* k_new, const void* v_n
                                         (hipStream_t)stream));
 }
 
+int32_t kvr_swap_back(const kvr_desc* desc, const float* scores, int64_t n_cap, void* k_ret, void* v_ret,
+                      int32_t* ret_pos, int32_t ret_cap, const int32_t* n_ctx, int32_t n_recent,
+                      float replace_rate, int32_t max_swaps, void* sketch_k, void* sketch_v,
+                      int32_t* vague_pos, const int32_t* n_vague, int32_t vague_cap, int32_t* n_swapped,
+                      int32_t* swap_log, void* stream) {
+  kvr::DevDesc d;
+  const int32_t rc = check_desc(desc, d);
+  if (rc != KVR_OK) return rc;
+  if (!scores || !k_ret || !v_ret || !ret_pos || !n_ctx || !sketch_k || !sketch_v || !vague_pos || !n_vague)
+    return KVR_ERR_INVALID_ARG;
+  if (!aligned16(k_ret) || !aligned16(v_ret) || !aligned16(sketch_k) || !aligned16(sketch_v))
+    return KVR_ERR_INVALID_ARG;
+  if (n_cap < 1 || n_cap > MAX_TOKENS || ret_cap < 1 || ret_cap > MAX_TOKENS || vague_cap < 1 ||
+      vague_cap > MAX_TOKENS || n_recent < 0)
+    return KVR_ERR_INVALID_ARG;
+  if (!(replace_rate > 0.f) || !(replace_rate < 3.0e38f)) return KVR_ERR_INVALID_ARG;   // also rejects NaN
+  if (max_swaps < 0 || max_swaps > 65536) return KVR_ERR_INVALID_ARG;
+  return finish(kvr::launch_swap_back(d, desc->dtype, scores, n_cap, k_ret, v_ret, ret_pos, ret_cap, n_ctx,
+                                      n_recent, replace_rate, max_swaps, sketch_k, sketch_v, vague_pos,
+                                      n_vague, vague_cap, n_swapped, swap_log, (hipStream_t)stream));
+}
+
 int32_t kvr_reconstruct(const kvr_desc* desc, const void* sketch_k, const void* sketch_v,
                         const int32_t* tok_pos, const int32_t* count, int32_t cap, void* k_out, void* v_out,
                         void* stream) {

@@ -96,6 +96,13 @@ hipError_t launch_step_update(const DevDesc& d, int dtype, const void* k_new, co
                               int32_t* vague_pos, int32_t* n_vague, int vague_cap, void* sk, void* sv,
                               hipStream_t st);
 
+// swap loop of Algorithm 3: at most max_swaps exchanges between the Candidate and the Vague part per unit
+hipError_t launch_swap_back(const DevDesc& d, int dtype, const float* scores, long long n_cap, void* k_ret,
+                            void* v_ret, int32_t* ret_pos, int ret_cap, const int32_t* n_ctx, int n_recent,
+                            float replace_rate, int max_swaps, void* sk, void* sv, int32_t* vague_pos,
+                            const int32_t* n_vague, int vague_cap, int32_t* n_swapped, int32_t* swap_log,
+                            hipStream_t st);
+
 hipError_t launch_encode(const DevDesc& d, int dtype, const void* k_src, const void* v_src, int src_rows,
                          const int32_t* src_slot, const int32_t* tok_pos, const int32_t* count, int cap,
                          void* sk, void* sv, int32_t* out_bucket, uint8_t* out_sign,

@@ -71,11 +71,18 @@ class LayerState:
                             self.evict_slot, self.evict_pos, self.n_evict, self.evict_cap, self.vague_pos,
                             self.n_vague, self.vague_cap, self.sketch_k, self.sketch_v)
 
-    def decode_step(self, k_new, v_new, q, *, bump_n_ctx=True, fused=None):
-        """append -> select -> encode -> attend.  n_ctx counts the new token from
-        here on; pass bump_n_ctx=False when several layers share one n_ctx tensor
-        that the caller advances once per step.  fused: use kvr_step_update for the
-        first three (default: whenever its size limits allow)."""
+    def swap_back(self, replace_rate=1.1, max_swaps=4, n_swapped=None, swap_log=None):
+        """The swap loop of Algorithm 3 on this layer's buffers."""
+        kvr.kvr_swap_back(self.desc, self.scores, self.n_cap, self.k_ret, self.v_ret, self.ret_pos,
+                          self.ret_cap, self.n_ctx, self.n_recent, replace_rate, max_swaps, self.sketch_k,
+                          self.sketch_v, self.vague_pos, self.n_vague, self.vague_cap, n_swapped, swap_log)
+
+    def decode_step(self, k_new, v_new, q, *, bump_n_ctx=True, fused=None, replace_rate=None, max_swaps=4):
+        """append -> select -> encode -> (swap loop, if replace_rate is given) ->
+        attend.  n_ctx counts the new token from here on; pass bump_n_ctx=False when
+        several layers share one n_ctx tensor that the caller advances once per
+        step.  fused: use kvr_step_update for the first three (default: whenever its
+        size limits allow)."""
         if bump_n_ctx:
             self.n_ctx += 1
         if fused is None:
@@ -86,6 +93,8 @@ class LayerState:
             self.append(k_new, v_new)
             self.select()
             self.encode()
+        if replace_rate is not None and max_swaps > 0:
+            self.swap_back(replace_rate, max_swaps)
         return self.attend(q)
 
     # -- building the state from a prompt ---------------------------------------
