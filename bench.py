@@ -123,6 +123,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--layers", type=int, default=None, help="debug: run fewer layers (result is then not the named workload)")
+    ap.add_argument("--replace-rate", type=float, default=None,
+                    help="also run the swap loop of Algorithm 3 in every step with this ReplaceRate (the paper "
+                         "fixes 1.1); off by default: the headline configuration evicts and encodes only")
+    ap.add_argument("--max-swaps", type=int, default=4, help="bound of the swap loop per unit and step")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=8)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -189,10 +193,12 @@ def main():
             log(f"[bench] layer {l + 1}/{L} compressed ({time.perf_counter() - t_setup:.1f} s)")
     torch.cuda.empty_cache()
 
+    swap_kw = {} if args.replace_rate is None else {"replace_rate": args.replace_rate, "max_swaps": args.max_swaps}
+
     def run_step(t):
         n_ctx.add_(1)
         for l in range(L):
-            layers[l].decode_step(knew[l][t], vnew[l][t], qs[l][t], bump_n_ctx=False)
+            layers[l].decode_step(knew[l][t], vnew[l][t], qs[l][t], bump_n_ctx=False, **swap_kw)
 
     for t in range(W):
         run_step(t)
@@ -210,7 +216,7 @@ def main():
             a, b = pairs[i]
             i += 1
             kvr.kvr_profile_events(a, b)
-            layers[l].decode_step(knew[l][t], vnew[l][t], qs[l][t], bump_n_ctx=False)
+            layers[l].decode_step(knew[l][t], vnew[l][t], qs[l][t], bump_n_ctx=False, **swap_kw)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
@@ -282,6 +288,12 @@ def main():
             "launches_timed": len(kern_ms),
         },
     }
+    if args.replace_rate is not None:
+        n_sw = torch.zeros(B, Hkv, dtype=torch.int32, device=dev)
+        layers[0].swap_back(args.replace_rate, args.max_swaps, n_sw)       # one more loop, to report its count
+        result["config"]["workload"] += f" + swap loop (ReplaceRate {args.replace_rate}, <= {args.max_swaps} per unit and step)"
+        result["swap_back"] = {"replace_rate": args.replace_rate, "max_swaps": args.max_swaps,
+                               "swaps_per_unit_after_last_step": float(n_sw.float().mean().item())}
     if args.layers is not None and args.layers != wl.layers:
         result["config"]["workload"] += f" [DEBUG: only {L} of {wl.layers} layers]"
     log(f"[bench] {steps_per_s:.2f} steps/s, {result['ms_per_step']:.3f} ms/step, "

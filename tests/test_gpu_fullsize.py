@@ -155,3 +155,51 @@ def test_c4_layer_in_bench_configuration():
         say("full size: max |out - dense over reconstruction| =", err, " max |out| =", big)
         assert err <= 2e-5 * big
         del Kall, Vall, logit, kh, vh
+
+    # ---- swap loop (Algorithm 3) at this size: the natural state after two steps,
+    #      then with a few Vague scores of the sampled units raised so that they swap
+    say("full size: swap loop")
+    MAXSW = 4
+    rng = np.random.default_rng(4)
+    for (b, h), st in zip(SAMPLED, states):
+        cand = [int(p) for p in st.ret_pos if 0 <= p < st.n_ctx - st.n_recent]
+        top = float(st.scores[cand].max())
+        for n, i in enumerate(rng.choice(len(st.vague_pos), size=3, replace=False)):
+            st.scores[st.vague_pos[i]] = np.float32(top * (2 + n // 2))
+        upload_unit(ls, b, h, st)
+    n_sw = torch.full((B, Hkv), -1, dtype=torch.int32, device=dev)
+    log = torch.full((B, Hkv, MAXSW, 2), -1, dtype=torch.int32, device=dev)
+    sk_before = ls.sketch_k.clone()
+    ls.swap_back(1.1, MAXSW, n_sw, log)
+    torch.cuda.synchronize()
+    for (b, h), st in zip(SAMPLED, states):
+        done = st.swap_back(1.1, MAXSW)
+        assert len(done) >= 3 and int(n_sw[b, h]) == len(done)
+        assert [tuple(x) for x in log[b, h, :len(done)].cpu().tolist()] == done
+        assert np.array_equal(ls.ret_pos[b, h].cpu().numpy(), st.ret_pos)
+        nv = int(ls.n_vague[b, h])
+        assert np.array_equal(ls.vague_pos[b, h, :nv].cpu().numpy(), st.vague_pos)
+        assert np.array_equal(U.to_np(ls.sketch_k[b, h]), st.SK) and np.array_equal(U.to_np(ls.sketch_v[b, h]), st.SV)
+        assert np.array_equal(U.to_np(ls.k_ret[b, h]), st.K_ret) and np.array_equal(U.to_np(ls.v_ret[b, h]), st.V_ret)
+    # every unit: counts in range, still a partition, and where the loop stopped by
+    # itself its exit condition holds: min Candidate score * 1.1 >= max Vague score (float32)
+    assert int(n_sw.min()) >= 0 and int(n_sw.max()) <= MAXSW
+    n_ctx = N + NSTEPS
+    cnt = torch.zeros(B, Hkv, n_ctx + 1, dtype=torch.int32, device=dev)
+    rp = ls.ret_pos.long()
+    cnt.scatter_add_(2, torch.where(rp >= 0, rp, torch.full_like(rp, n_ctx)), torch.ones_like(rp, dtype=torch.int32))
+    nv = int(ls.n_vague.max())
+    vp = ls.vague_pos[:, :, :nv].long()
+    live = torch.arange(nv, device=dev).view(1, 1, nv) < ls.n_vague.unsqueeze(-1)
+    cnt.scatter_add_(2, torch.where(live, vp, torch.full_like(vp, n_ctx)), torch.ones_like(vp, dtype=torch.int32))
+    assert bool((cnt[:, :, :n_ctx] == 1).all())
+    cand = (rp >= 0) & (rp < n_ctx - wl.n_recent)
+    sc_c = ls.scores.gather(2, rp.clamp(min=0))
+    cmin = torch.where(cand, sc_c, torch.full_like(sc_c, float("inf"))).amin(dim=2)
+    sc_v = ls.scores.gather(2, vp)
+    vmax = torch.where(live, sc_v, torch.full_like(sc_v, float("-inf"))).amax(dim=2)
+    stopped = n_sw < MAXSW
+    assert bool(((cmin * torch.tensor(1.1, dtype=torch.float32, device=dev) >= vmax) | ~stopped).all())
+    untouched = n_sw == 0
+    assert bool((ls.sketch_k == sk_before)[untouched].all())
+    say("full size: swaps per unit: min", int(n_sw.min()), "max", int(n_sw.max()), "mean", float(n_sw.float().mean()))
