@@ -126,6 +126,9 @@ def main():
     ap.add_argument("--replace-rate", type=float, default=None,
                     help="also run the swap loop of Algorithm 3 in every step with this ReplaceRate (the paper "
                          "fixes 1.1); off by default: the headline configuration evicts and encodes only")
+    ap.add_argument("--layer-budget-ramp", type=float, default=0.0,
+                    help="non-uniform per-layer budgets: layer l gets budget * (1 - s + 2 s l / (L - 1)), the same "
+                         "total; 0 (default) = the uniform budget of the headline configuration")
     ap.add_argument("--max-swaps", type=int, default=4, help="bound of the swap loop per unit and step")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=8)
@@ -168,22 +171,30 @@ def main():
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_compress_ms = 0.0
     t_setup = time.perf_counter()
+    s_ramp = args.layer_budget_ramp
+    if s_ramp != 0.0:
+        ratios = [1.0 - s_ramp + 2.0 * s_ramp * l / max(wl.layers - 1, 1) for l in range(wl.layers)]
+        wl_layers = S.layer_budgets(wl, ratios)
+    else:
+        wl_layers = [wl] * wl.layers
     for l in range(L):
+        wll = wl_layers[l]
         params = kvr.kvr_hash_params_from_seed(S.BASE_SEED + l, wl.r)
-        d = kvr.make_desc(B, Hq, Hkv, wl.r, wl.w, wl.torch_dtype, hash_params=params)
-        Kf, Vf = S.kv_layer(wl, l, device=dev)
-        qall = S.queries_many(wl, l, 0, T + 1, device=dev)          # q[0] initialises the scores
-        ls, _ = LayerState.from_prefill(d, Kf, Vf, qall[0].contiguous(), n_recent=wl.n_recent,
-                                        k_candidate=wl.n_candidate, max_new_tokens=T, ws_attend=ws_att,
+        d = kvr.make_desc(B, Hq, Hkv, wl.r, wll.w, wl.torch_dtype, hash_params=params)
+        Kf, Vf = S.kv_layer(wll, l, device=dev)
+        qall = S.queries_many(wll, l, 0, T + 1, device=dev)          # q[0] initialises the scores
+        ls, _ = LayerState.from_prefill(d, Kf, Vf, qall[0].contiguous(), n_recent=wll.n_recent,
+                                        k_candidate=wll.n_candidate, max_new_tokens=T, ws_attend=ws_att,
                                         ws_encode=ws_enc, n_ctx=n_ctx, timers=(ev0, ev1))
         torch.cuda.synchronize()
         t_compress_ms += ev0.elapsed_time(ev1)
         ne = ls.n_evict.min().item()
-        if ne != wl.n_vague0 or ls.n_evict.max().item() != wl.n_vague0:
-            raise RuntimeError(f"layer {l}: prompt compression evicted {ne}, expected {wl.n_vague0}")
-        ws_att, ws_enc = ls.ws_attend, ls.ws_encode
+        if ne != wll.n_vague0 or ls.n_evict.max().item() != wll.n_vague0:
+            raise RuntimeError(f"layer {l}: prompt compression evicted {ne}, expected {wll.n_vague0}")
+        if s_ramp == 0.0:            # layers of one size share the workspaces
+            ws_att, ws_enc = ls.ws_attend, ls.ws_encode
         del Kf, Vf
-        kn, vn = S.kv_layer(wl, l, wl.context, wl.context + T, device=dev)      # [B, Hkv, T, D]
+        kn, vn = S.kv_layer(wll, l, wl.context, wl.context + T, device=dev)      # [B, Hkv, T, D]
         knew.append(kn.permute(2, 0, 1, 3).contiguous())
         vnew.append(vn.permute(2, 0, 1, 3).contiguous())
         qs.append(qall[1:].contiguous())
@@ -227,7 +238,7 @@ def main():
 
     # sanity of the state after the run: one eviction per unit per step
     nv = layers[0].n_vague
-    if nv.min().item() != wl.n_vague0 + T or nv.max().item() != wl.n_vague0 + T:
+    if nv.min().item() != wl_layers[0].n_vague0 + T or nv.max().item() != wl_layers[0].n_vague0 + T:
         raise RuntimeError("bookkeeping drifted: n_vague is not a0 + steps")
     if not torch.isfinite(layers[-1].out).all():
         raise RuntimeError("non-finite attention output")
@@ -237,9 +248,9 @@ def main():
                                                + 4 * wl.context)
     steps_per_s = K_steps / elapsed
     n_mid = wl.context + W + (K_steps + 1) // 2
-    bytes_unit = algorithmic_bytes_per_unit(wl, n_mid)
-    bytes_launch = bytes_unit * wl.units_per_layer
-    bytes_step = bytes_launch * L
+    bytes_layer = [algorithmic_bytes_per_unit(wl_layers[l], n_mid) * wl.units_per_layer for l in range(L)]
+    bytes_launch = sum(bytes_layer) / L            # per launch (mean over the layers when budgets differ)
+    bytes_step = sum(bytes_layer)
     avg_kern_s = (sum(kern_ms) / len(kern_ms)) * 1e-3
     achieved = bytes_launch / avg_kern_s / 1e9
     result = {
@@ -294,6 +305,9 @@ def main():
         result["config"]["workload"] += f" + swap loop (ReplaceRate {args.replace_rate}, <= {args.max_swaps} per unit and step)"
         result["swap_back"] = {"replace_rate": args.replace_rate, "max_swaps": args.max_swaps,
                                "swaps_per_unit_after_last_step": float(n_sw.float().mean().item())}
+    if s_ramp != 0.0:
+        result["config"]["workload"] += (f" + per-layer budgets {wl_layers[0].budget:.4f} .. {wl_layers[L - 1].budget:.4f} "
+                                         f"(w {wl_layers[0].w} .. {wl_layers[L - 1].w})")
     if args.layers is not None and args.layers != wl.layers:
         result["config"]["workload"] += f" [DEBUG: only {L} of {wl.layers} layers]"
     log(f"[bench] {steps_per_s:.2f} steps/s, {result['ms_per_step']:.3f} ms/step, "

@@ -109,6 +109,27 @@ WORKLOADS = {
 }
 
 
+def layer_budgets(wl: Workload, ratios):
+    """Non-uniform memory budgets across layers (the paper derives the allocation
+    ratio of a layer from the Fisher information of its key and value weights;
+    here the ratios are an input).  Returns one Workload per layer with
+    budget_l = wl.budget * ratios[l] / mean(ratios), so that the total over the
+    layers stays wl.budget * layers (up to the per-layer rounding to tokens).
+    Everything else (shapes, seeds, data) is the layer's own as before."""
+    import dataclasses
+    ratios = [float(x) for x in ratios]
+    if len(ratios) != wl.layers or min(ratios) <= 0:
+        raise ValueError("one positive ratio per layer")
+    mean = sum(ratios) / len(ratios)
+    out = []
+    for x in ratios:
+        b = wl.budget * x / mean
+        if not (0.0 < b <= 1.0):
+            raise ValueError(f"layer budget {b} outside (0, 1]")
+        out.append(dataclasses.replace(wl, budget=b))
+    return out
+
+
 def small_workload(name="tiny", *, layers=1, batch=2, n_q_heads=4, n_kv_heads=2,
                    context=300, dtype="bf16", budget=0.25, r=3, needles=3,
                    outlier_channels=2, steps=4, cfg_id=99, needle_spread=False):

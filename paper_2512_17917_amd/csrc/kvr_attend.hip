@@ -324,16 +324,14 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
         M = mn;
       }
     }
+    // the wave's maximum first (no exponentials), then one rescaling per lane and a plain sum
+    float Mw = M;
 #pragma unroll
-    for (int off = 1; off < WAVE; off <<= 1) {
-      const float M2 = __shfl_xor(M, off), L2 = __shfl_xor(L, off);
-      const float mn = fmaxf(M, M2);
-      const float e1 = (M == -__builtin_inff()) ? 0.f : expf(M - mn);
-      const float e2 = (M2 == -__builtin_inff()) ? 0.f : expf(M2 - mn);
-      L = L * e1 + L2 * e2;
-      M = mn;
-    }
-    if (lane == 0) { sM[g] = M; sL[g] = L; }
+    for (int off = 1; off < WAVE; off <<= 1) Mw = fmaxf(Mw, __shfl_xor(Mw, off));
+    float Lw = (L > 0.f) ? L * expf(M - Mw) : 0.f;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) Lw += __shfl_xor(Lw, off);
+    if (lane == 0) { sM[g] = Mw; sL[g] = Lw; }
   }
   __syncthreads();
 

@@ -504,7 +504,10 @@ def test_decode_steps_follow_the_oracle(kvr, LayerState, name, fused):
                               cfg_id=98)
         nsteps = 3
     say("decode steps", name)
-    layer = 0
+    run_decode_steps(kvr, LayerState, wl, 0, nsteps, fused)
+
+
+def run_decode_steps(kvr, LayerState, wl, layer, nsteps, fused):
     units = [(b, h) for b in range(wl.batch) for h in range(wl.n_kv_heads)]
     states = U.oracle_units_from_workload(wl, layer, units, extra_tokens=nsteps + 2)
     params = states[0].params

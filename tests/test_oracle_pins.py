@@ -718,3 +718,23 @@ def test_swap_loop_exit_condition_and_partition():
     st2.scores[st2.vague_pos] += 10.0          # every Vague token now outranks every Candidate
     assert len(st2.swap_back(1.1, 3)) == 3
     assert len(st2.swap_back(1.1, 0)) == 0
+
+
+# ------------------------------------------------------------------ input recipe: per-layer budgets
+def test_layer_budgets_preserve_the_total():
+    import kvr_synth as S
+    wl = S.WORKLOADS["c4"]
+    ratios = [1.0 + 0.15 * (2 * l / (wl.layers - 1) - 1) for l in range(wl.layers)]
+    per = S.layer_budgets(wl, ratios)
+    assert len(per) == wl.layers
+    total = sum(p.budget_tokens for p in per)
+    assert abs(total - wl.layers * wl.budget_tokens) <= wl.layers          # rounding to whole tokens only
+    for p, x in zip(per, ratios):
+        assert abs(p.budget - wl.budget * x) < 1e-12                         # mean ratio is 1 here
+        assert p.n_retained + p.sketch_slots == p.budget_tokens
+        assert p.n_vague0 + p.n_retained == wl.context
+    assert per[0].w < wl.w < per[-1].w
+    with pytest.raises(ValueError):
+        S.layer_budgets(wl, [1.0] * (wl.layers - 1))
+    with pytest.raises(ValueError):
+        S.layer_budgets(wl, [8.0] + [0.01] * (wl.layers - 1))
