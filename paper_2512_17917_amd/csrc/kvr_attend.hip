@@ -255,7 +255,6 @@ __global__ __launch_bounds__(256) void attend_main_kernel(DevDesc d, AttendArgs 
 // ---------------------------------------------------------------------------
 // merge kernel
 // ---------------------------------------------------------------------------
-constexpr int CMB_MAXW = 2048;     // slice weights kept in LDS when n_slices * G fits
 
 template <int G>
 __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendArgs a) {
@@ -263,9 +262,7 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
   const int b = unit / d.Hkv, hk = unit % d.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   __shared__ float sM[G], sL[G];
-  __shared__ float sW[CMB_MAXW];
   const float* pml = a.part_ml + (size_t)unit * a.n_slices * G * 2;
-  const bool w_in_lds = a.n_slices * G <= CMB_MAXW;
 
   // ---- score pass, first half: everything that does not depend on the global
   //      statistics is requested before they are formed (token positions, the
@@ -369,32 +366,50 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
     }
   }
 
-  // ---- the unit's output: first workgroup of the unit ---------------------------
-  if (blockIdx.x == 0) {
-    if (w_in_lds) {
-      for (int idx = tid; idx < a.n_slices * G; idx += 256) {
-        const int g = idx % G;
-        const float ms = pml[idx * 2], ls = pml[idx * 2 + 1];
-        sW[idx] = (ls > 0.f) ? expf(ms - sM[g]) : 0.f;
-      }
-      __syncthreads();
-    }
+  // ---- the unit's output: spread over the first nb workgroups of the unit (a power
+  //      of two <= 8): workgroup bx takes G*D/nb output elements, four threads per
+  //      element, each summing every fourth slice with eight loads in flight; a
+  //      unit cut into many slices (few units, long lists) would otherwise spend
+  //      its time in one thread's walk over the slices. ------------------------------
+  int nb = 1;
+  while (nb * 2 <= 8 && nb * 2 <= (int)gridDim.x) nb *= 2;
+  if ((int)blockIdx.x < nb) {
+    __shared__ float sO[4][64];                // [slice quarter][output element of this round]
+    const int per_wg = G * D / nb;            // 16 .. 1024, multiple of 16
     const float* po = a.part_o + (size_t)unit * a.n_slices * G * D;
-    for (int idx = tid; idx < G * D; idx += 256) {
-      const int g = idx / D;
-      const float M = sM[g], L = sL[g];
+    for (int o0 = 0; o0 < per_wg; o0 += 64) {
+      const int ol = o0 + (tid & 63), sq = tid >> 6;
+      const int idx = blockIdx.x * per_wg + ol;
+      const bool live = ol < per_wg;
+      const int g = live ? idx / D : 0;
+      const float M = sM[g];
       float o = 0.f;
-      for (int s = 0; s < a.n_slices; ++s) {
-        float wgt;
-        if (w_in_lds) {
-          wgt = sW[s * G + g];
-        } else {
-          const float ms = pml[(s * G + g) * 2], ls = pml[(s * G + g) * 2 + 1];
-          wgt = (ls > 0.f) ? expf(ms - M) : 0.f;
+      if (live) {
+        for (int s0 = sq; s0 < a.n_slices; s0 += 4 * 8) {
+          float v[8], wgt[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int s_ = s0 + 4 * j;
+            v[j] = 0.f;
+            wgt[j] = 0.f;
+            if (s_ < a.n_slices) {
+              v[j] = po[(size_t)s_ * G * D + idx];
+              const float ms = pml[(s_ * G + g) * 2], ls = pml[(s_ * G + g) * 2 + 1];
+              wgt[j] = (ls > 0.f) ? expf(ms - M) : 0.f;
+            }
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o = fmaf(v[j], wgt[j], o);
         }
-        o = fmaf(po[(size_t)s * G * D + idx], wgt, o);
       }
-      a.out[((size_t)b * d.Hq + (size_t)hk * G) * D + idx] = (L > 0.f) ? o / L : 0.f;
+      __syncthreads();                         // previous round's readers are done with sO
+      sO[sq][tid & 63] = o;
+      __syncthreads();
+      if (sq == 0 && live) {
+        const float tot = (sO[0][tid] + sO[1][tid]) + (sO[2][tid] + sO[3][tid]);
+        const float L = sL[g];
+        a.out[((size_t)b * d.Hq + (size_t)hk * G) * D + idx] = (L > 0.f) ? tot / L : 0.f;
+      }
     }
   }
 }
@@ -469,7 +484,11 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
   // The retained kernel is bound by HBM, the staged kernel by the vector ALUs and
   // LDS, and their registers and LDS fit on a CU together: run them side by side,
   // the retained kernel on a side stream forked from and joined back into `st`.
-  SideStream* side = (plan.mfma_retained && plan.staged && overlap_enabled()) ? side_stream() : nullptr;
+  // Only when the staged kernel fills the chip several times over: a launch of a few workgroups is
+  // short, the fork and join then cost more than the overlap saves, and the retained kernel is better
+  // off with a launch as wide as its item count than with one workgroup per CU.
+  const bool big = (long long)units * plan.n_vslices >= 2ll * cu_count();
+  SideStream* side = (plan.mfma_retained && plan.staged && big && overlap_enabled()) ? side_stream() : nullptr;
   if (side != nullptr) {
     e = hipEventRecord(side->fork, st);
     if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
