@@ -84,10 +84,22 @@ __global__ __launch_bounds__(SEL_THREADS) void step_update_kernel(
     int evict_cap, int32_t* __restrict__ vague_pos, int32_t* __restrict__ n_vague, int vague_cap,
     T* __restrict__ sk, T* __restrict__ sv) {
   const int unit = blockIdx.x;
-  (void)append_body<T, SEL_THREADS>(d, unit, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap);
+  // the slot positions are read once and serve both the search for a free slot and
+  // the selection keys (the token appended in between is Recent: for the selection
+  // its slot might as well still be empty)
+  int pre[SEL_KPT];
+  {
+    const int32_t* rp = ret_pos + (size_t)unit * ret_cap;
+#pragma unroll
+    for (int j = 0; j < SEL_KPT; ++j) {
+      const int s = j * SEL_THREADS + threadIdx.x;
+      pre[j] = (s < ret_cap) ? rp[s] : 0;
+    }
+  }
+  (void)append_body_pre<T, SEL_THREADS, SEL_KPT>(d, unit, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap, pre);
   __syncthreads();          // the new row and its ret_pos entry are visible to the whole workgroup
   select_body<true>(d, unit, scores, n_cap, ret_pos, ret_cap, n_ctx, n_recent, k_cand, evict_slot, evict_pos,
-                    n_evict, evict_cap, vague_pos, n_vague, vague_cap);
+                    n_evict, evict_cap, vague_pos, n_vague, vague_cap, pre);
   __syncthreads();          // the eviction list and its count are visible
   encode_small_body<T>(d, unit, k_ret, v_ret, ret_cap, evict_slot, evict_pos, n_evict, evict_cap, sk, sv,
                        nullptr, nullptr);

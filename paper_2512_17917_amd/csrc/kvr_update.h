@@ -26,6 +26,7 @@ struct SelShared {
   int wsum[SEL_WAVES];
   int wscan[4];
   int krem, cnt, base;
+  int nlist, list[SEL_SMALL];        // small eviction counts: the evicted slots, in any order
 };
 
 // ---------------------------------------------------------------------------
@@ -75,9 +76,58 @@ __device__ __forceinline__ int append_body(const DevDesc& d, int unit, const T* 
   return s;
 }
 
+// The same with the slot positions already in registers (pre[j] = ret_pos of slot
+// j * NT + tid, or 0 for slots past ret_cap): no scan of ret_pos.
+template <typename T, int NT, int KPT>
+__device__ __forceinline__ int append_body_pre(const DevDesc& d, int unit, const T* __restrict__ k_new,
+                                               const T* __restrict__ v_new, const int32_t* __restrict__ n_ctx,
+                                               T* __restrict__ k_ret, T* __restrict__ v_ret,
+                                               int32_t* __restrict__ ret_pos, int ret_cap, const int (&pre)[KPT]) {
+  constexpr int VEC = Store<T>::VEC;
+  constexpr int LPT = D / VEC;
+  const int tid = threadIdx.x;
+  int32_t* rp = ret_pos + (size_t)unit * ret_cap;
+  __shared__ int s_free;
+  if (tid == 0) s_free = 0x7fffffff;
+  __syncthreads();
+  int mine = 0x7fffffff;
+#pragma unroll
+  for (int j = KPT - 1; j >= 0; --j) {
+    const int s = j * NT + tid;
+    if (s < ret_cap && pre[j] < 0) mine = s;
+  }
+  if (mine != 0x7fffffff) atomicMin(&s_free, mine);
+  __syncthreads();
+  const int s = s_free;
+  if (s >= ret_cap) return -1;
+  const size_t dst = ((size_t)unit * ret_cap + s) * D;
+  if (tid < LPT) {
+    const uint4 v = *reinterpret_cast<const uint4*>(k_new + (size_t)unit * D + tid * VEC);
+    *reinterpret_cast<uint4*>(k_ret + dst + tid * VEC) = v;
+  } else if (tid < 2 * LPT) {
+    const int l2 = tid - LPT;
+    const uint4 v = *reinterpret_cast<const uint4*>(v_new + (size_t)unit * D + l2 * VEC);
+    *reinterpret_cast<uint4*>(v_ret + dst + l2 * VEC) = v;
+  }
+  if (tid == 0) rp[s] = n_ctx[unit / d.Hkv] - 1;
+  return s;
+}
+
 // ---------------------------------------------------------------------------
 // select
 // ---------------------------------------------------------------------------
+// key of a slot whose position is already known
+__device__ __forceinline__ bool pos_key(int pos, const float* __restrict__ sc, int slot, int ret_cap,
+                                        int recent_from, long long n_cap, unsigned long long& key) {
+  if (slot >= ret_cap) return false;
+  if (pos < 0 || pos >= recent_from || pos >= n_cap) return false;
+  uint32_t b = __float_as_uint(sc[pos]);
+  if (b == 0x80000000u) b = 0u;                                   // -0 ranks as +0
+  const uint32_t mono = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
+  key = ((unsigned long long)mono << 32) | (uint32_t)(~(uint32_t)pos);
+  return true;
+}
+
 __device__ __forceinline__ bool slot_key(const int32_t* __restrict__ rp, const float* __restrict__ sc,
                                          int slot, int ret_cap, int recent_from, long long n_cap,
                                          unsigned long long& key) {
@@ -148,12 +198,16 @@ __device__ __forceinline__ void pick_digit(SelShared& sh, int byte) {
 // Workgroup of SEL_THREADS threads.  REG: ret_cap <= SEL_REG_SLOTS, keys live in
 // registers.  Writes the eviction lists, frees the slots, appends to the Vague
 // list, sets n_evict (negative = needed count on overflow, nothing evicted).
+// pre (REG only, may be null): positions of this thread's slots as they were
+// before a token was appended in this same launch; the appended token is Recent
+// and therefore ranks like an empty slot, so the stale value serves.
 template <bool REG>
 __device__ __forceinline__ void select_body(
     const DevDesc& d, int unit, const float* __restrict__ scores, long long n_cap,
     int32_t* __restrict__ ret_pos, int ret_cap, const int32_t* __restrict__ n_ctx, int n_recent, int k_cand,
     int32_t* __restrict__ evict_slot, int32_t* __restrict__ evict_pos, int32_t* __restrict__ n_evict,
-    int evict_cap, int32_t* __restrict__ vague_pos, int32_t* __restrict__ n_vague, int vague_cap) {
+    int evict_cap, int32_t* __restrict__ vague_pos, int32_t* __restrict__ n_vague, int vague_cap,
+    const int* pre = nullptr) {
   const int b = unit / d.Hkv;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -175,7 +229,7 @@ __device__ __forceinline__ void select_body(
     }
   };
 
-  if (tid == 0) { sh.cnt = 0; sh.base = 0; sh.prefix = 0ull; sh.krem = k_cand; }
+  if (tid == 0) { sh.cnt = 0; sh.base = 0; sh.prefix = 0ull; sh.krem = k_cand; sh.nlist = 0; }
   __syncthreads();
   {
     int c = 0;
@@ -183,7 +237,8 @@ __device__ __forceinline__ void select_body(
 #pragma unroll
       for (int j = 0; j < SEL_KPT; ++j) {
         unsigned long long key = KEY_NONE;
-        const bool ok = slot_key(rp, sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key);
+        const bool ok = pre ? pos_key(pre[j], sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key)
+                            : slot_key(rp, sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key);
         rkey[j] = ok ? key : KEY_NONE;
         c += ok ? 1 : 0;
       }
@@ -242,6 +297,35 @@ __device__ __forceinline__ void select_body(
       pick_digit(sh, byte);
     }
     cut = sh.prefix - 1;       // prefix = the k-th largest key; it stays
+  }
+
+  if (REG && n_e <= SEL_SMALL) {
+    // a handful of evictions: the owners put their slots into a short list (any
+    // order), and each then takes the rank of its slot as its place in the output
+    if constexpr (REG) {
+#pragma unroll
+      for (int j = 0; j < SEL_KPT; ++j)
+        if (rkey[j] != KEY_NONE && rkey[j] <= cut) sh.list[atomicAdd(&sh.nlist, 1)] = j * SEL_THREADS + tid;
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < SEL_KPT; ++j) {
+        if (rkey[j] != KEY_NONE && rkey[j] <= cut) {
+          const int slot = j * SEL_THREADS + tid;
+          int idx = 0;
+          for (int x = 0; x < n_e; ++x) idx += (sh.list[x] < slot) ? 1 : 0;
+          const int pos = key_pos(rkey[j]);
+          evict_slot[(size_t)unit * evict_cap + idx] = slot;
+          evict_pos[(size_t)unit * evict_cap + idx] = pos;
+          rp[slot] = -1;
+          if (vague_pos && n_vague) vague_pos[(size_t)unit * vague_cap + nv_old + idx] = pos;
+        }
+      }
+    }
+    if (tid == 0) {
+      n_evict[unit] = n_e;
+      if (vague_pos && n_vague) n_vague[unit] = nv_old + n_e;
+    }
+    return;
   }
 
 #pragma unroll
