@@ -85,7 +85,9 @@ __global__ __launch_bounds__(256) void encode_hash_kernel(
 //      slot, and the highest lane of each slot moves the cursor on.  Waves work
 //      on disjoint rows of the table and on disjoint ranges of the output, so
 //      there is no barrier inside the walk.
-// A slot's ordinals come out ascending, which fixes the summation order.
+// A slot's tokens come out in list order, which fixes the summation order.  What
+// is written per token is its source row with the sign of this sketch row in
+// the top bit (source rows are below 2^30).
 constexpr int SORT_MAX_SEGS = 16;
 constexpr int SORT_LDS_INTS = 15360;       // 60 KB of table: segs * w + w <= this
 
@@ -98,13 +100,14 @@ static int sort_segments(int w) {
 
 __global__ __launch_bounds__(SORT_MAX_SEGS * WAVE) void encode_sort_kernel(
     DevDesc d, const int32_t* __restrict__ count, int cap, const int32_t* __restrict__ ws_bucket,
+    const int32_t* __restrict__ src_slot, const int32_t* __restrict__ tok_pos,
     int32_t* __restrict__ ws_order, int32_t* __restrict__ ws_start) {
   extern __shared__ int s_tab[];             // [segs][w] counts / cursors, then [w] totals / starts
   const int w = d.w;
   const int segs = blockDim.x / WAVE;
   int* s_tot = s_tab + segs * w;
   const int ur = blockIdx.x;                 // unit * r + row
-  const int unit = ur / d.r;
+  const int unit = ur / d.r, row = ur % d.r;
   const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
   const int cnt = clampi(count[unit], 0, cap);
   const int32_t* bk = ws_bucket + (size_t)ur * cap;
@@ -158,6 +161,13 @@ __global__ __launch_bounds__(SORT_MAX_SEGS * WAVE) void encode_sort_kernel(
   for (int e0 = lo; e0 < hi; e0 += WAVE) {
     const int e = e0 + lane;
     const int s = (e < hi) ? bk[e] : -1;
+    // what the accumulation needs of this token, so that it does not have to chase
+    // the ordinal: its source row and, in the top bit, whether g_row(J) = -1
+    int rec = 0;
+    if (s >= 0) {
+      rec = src_slot[(size_t)unit * cap + e];
+      if (sign_neg(d, row, tok_pos[(size_t)unit * cap + e])) rec |= (int)0x80000000u;
+    }
     int lower = 0;
     bool higher = false;
 #pragma unroll 8
@@ -169,7 +179,7 @@ __global__ __launch_bounds__(SORT_MAX_SEGS * WAVE) void encode_sort_kernel(
     }
     if (s >= 0) {
       const int dst = cur[s] + lower;
-      order[dst] = e;
+      order[dst] = rec;
       if (!higher) cur[s] = dst + 1;       // read above, written here by one lane per slot: same wave, program order
     }
     __builtin_amdgcn_wave_barrier();
@@ -190,8 +200,7 @@ __device__ __forceinline__ void load_pair(const bf16_t* p, float& a, float& b) {
 // segment, lanes across channels (2 per lane).
 template <typename T>
 __global__ __launch_bounds__(256) void encode_accum_kernel(
-    DevDesc d, const T* __restrict__ k_src, const T* __restrict__ v_src, int src_rows,
-    const int32_t* __restrict__ src_slot, const int32_t* __restrict__ tok_pos, int cap,
+    DevDesc d, const T* __restrict__ k_src, const T* __restrict__ v_src, int src_rows, int cap,
     const int32_t* __restrict__ ws_order, const int32_t* __restrict__ ws_start, T* __restrict__ sk,
     T* __restrict__ sv) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -211,13 +220,13 @@ __global__ __launch_bounds__(256) void encode_accum_kernel(
     int my_slot = 0;
     bool my_neg = false;
     if (p0 + lane < hi) {
-      const int e = order[p0 + lane];
-      my_slot = src_slot[(size_t)unit * cap + e];
-      my_neg = sign_neg(d, row, tok_pos[(size_t)unit * cap + e]);
+      const int rec = order[p0 + lane];
+      my_slot = rec & 0x7fffffff;
+      my_neg = rec < 0;
     }
     const unsigned long long negs = __ballot(my_neg);
     const int n = min(WAVE, hi - p0);
-#pragma unroll 8
+#pragma unroll 16
     for (int j = 0; j < n; ++j) {
       const int slot = __shfl(my_slot, j);
       const bool neg = (negs >> j) & 1ull;
@@ -261,13 +270,13 @@ static hipError_t launch_t(const DevDesc& d, const void* k_src, const void* v_sr
   {
     const int segs = sort_segments(d.w);
     hipLaunchKernelGGL(encode_sort_kernel, dim3(units * d.r), dim3(segs * WAVE),
-                       (size_t)(segs + 1) * d.w * sizeof(int), st, d, count, cap, ws_bucket, ws_order, ws_start);
+                       (size_t)(segs + 1) * d.w * sizeof(int), st, d, count, cap, ws_bucket, src_slot, tok_pos,
+                       ws_order, ws_start);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(encode_accum_kernel<T>, dim3((d.w + 3) / 4, d.r, units), dim3(256), 0, st, d,
-                     (const T*)k_src, (const T*)v_src, src_rows, src_slot, tok_pos, cap, ws_order, ws_start,
-                     (T*)sk, (T*)sv);
+                     (const T*)k_src, (const T*)v_src, src_rows, cap, ws_order, ws_start, (T*)sk, (T*)sv);
   return hipGetLastError();
 }
 

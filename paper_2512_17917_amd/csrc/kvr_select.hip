@@ -24,13 +24,13 @@
 
 namespace kvr {
 
-template <bool REG>
+template <bool REG, int KPT>
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(
     DevDesc d, const float* __restrict__ scores, long long n_cap, int32_t* __restrict__ ret_pos,
     int ret_cap, const int32_t* __restrict__ n_ctx, int n_recent, int k_cand,
     int32_t* __restrict__ evict_slot, int32_t* __restrict__ evict_pos, int32_t* __restrict__ n_evict,
     int evict_cap, int32_t* __restrict__ vague_pos, int32_t* __restrict__ n_vague, int vague_cap) {
-  select_body<REG>(d, blockIdx.x, scores, n_cap, ret_pos, ret_cap, n_ctx, n_recent, k_cand, evict_slot,
+  select_body<REG, KPT>(d, blockIdx.x, scores, n_cap, ret_pos, ret_cap, n_ctx, n_recent, k_cand, evict_slot,
                    evict_pos, n_evict, evict_cap, vague_pos, n_vague, vague_cap);
 }
 
@@ -38,14 +38,15 @@ hipError_t launch_select(const DevDesc& d, const float* scores, long long n_cap,
                          int ret_cap, const int32_t* n_ctx, int n_recent, int k_candidate,
                          int32_t* evict_slot, int32_t* evict_pos, int32_t* n_evict, int evict_cap,
                          int32_t* vague_pos, int32_t* n_vague, int vague_cap, hipStream_t st) {
-  if (ret_cap <= SEL_REG_SLOTS)
-    hipLaunchKernelGGL(select_kernel<true>, dim3(d.B * d.Hkv), dim3(SEL_THREADS), 0, st, d, scores, n_cap,
-                       ret_pos, ret_cap, n_ctx, n_recent, k_candidate, evict_slot, evict_pos, n_evict,
-                       evict_cap, vague_pos, n_vague, vague_cap);
-  else
-    hipLaunchKernelGGL(select_kernel<false>, dim3(d.B * d.Hkv), dim3(SEL_THREADS), 0, st, d, scores, n_cap,
-                       ret_pos, ret_cap, n_ctx, n_recent, k_candidate, evict_slot, evict_pos, n_evict,
-                       evict_cap, vague_pos, n_vague, vague_cap);
+  const dim3 grid(d.B * d.Hkv), block(SEL_THREADS);
+#define KVR_LAUNCH_SELECT(REG, KPT)                                                                            \
+  hipLaunchKernelGGL((select_kernel<REG, KPT>), grid, block, 0, st, d, scores, n_cap, ret_pos, ret_cap, n_ctx, \
+                     n_recent, k_candidate, evict_slot, evict_pos, n_evict, evict_cap, vague_pos, n_vague,     \
+                     vague_cap)
+  if (ret_cap <= SEL_THREADS * 8) KVR_LAUNCH_SELECT(true, 8);
+  else if (ret_cap <= SEL_THREADS * 32) KVR_LAUNCH_SELECT(true, 32);
+  else KVR_LAUNCH_SELECT(false, 1);
+#undef KVR_LAUNCH_SELECT
   return hipGetLastError();
 }
 

@@ -195,13 +195,14 @@ __device__ __forceinline__ void pick_digit(SelShared& sh, int byte) {
   __syncthreads();
 }
 
-// Workgroup of SEL_THREADS threads.  REG: ret_cap <= SEL_REG_SLOTS, keys live in
-// registers.  Writes the eviction lists, frees the slots, appends to the Vague
+// Workgroup of SEL_THREADS threads.  REG: ret_cap <= SEL_THREADS * KPT, keys live
+// in registers (KPT per thread: 8 for the retained slots of a decode step, 32 for
+// a 32k prompt).  Writes the eviction lists, frees the slots, appends to the Vague
 // list, sets n_evict (negative = needed count on overflow, nothing evicted).
 // pre (REG only, may be null): positions of this thread's slots as they were
 // before a token was appended in this same launch; the appended token is Recent
 // and therefore ranks like an empty slot, so the stale value serves.
-template <bool REG>
+template <bool REG, int KPT = SEL_KPT>
 __device__ __forceinline__ void select_body(
     const DevDesc& d, int unit, const float* __restrict__ scores, long long n_cap,
     int32_t* __restrict__ ret_pos, int ret_cap, const int32_t* __restrict__ n_ctx, int n_recent, int k_cand,
@@ -218,7 +219,7 @@ __device__ __forceinline__ void select_body(
   __shared__ SelShared sh;
 
   // keys of this thread's slots: slot = j * SEL_THREADS + tid
-  unsigned long long rkey[REG ? SEL_KPT : 1];
+  unsigned long long rkey[REG ? KPT : 1];
   const int n_chunks = (ret_cap + SEL_THREADS - 1) / SEL_THREADS;
   auto get_key = [&](int j, unsigned long long& key) -> bool {
     if constexpr (REG) {
@@ -235,7 +236,7 @@ __device__ __forceinline__ void select_body(
     int c = 0;
     if constexpr (REG) {
 #pragma unroll
-      for (int j = 0; j < SEL_KPT; ++j) {
+      for (int j = 0; j < KPT; ++j) {
         unsigned long long key = KEY_NONE;
         const bool ok = pre ? pos_key(pre[j], sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key)
                             : slot_key(rp, sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key);
@@ -272,7 +273,7 @@ __device__ __forceinline__ void select_body(
     for (int it = 0; it < n_e; ++it) {
       unsigned long long mine = KEY_NONE;
 #pragma unroll
-      for (int j = 0; j < (REG ? SEL_KPT : 1); ++j) {
+      for (int j = 0; j < (REG ? KPT : 1); ++j) {
         const unsigned long long key = rkey[j];
         if (key != KEY_NONE && (!have || key > last) && key < mine) mine = key;
       }
@@ -286,7 +287,7 @@ __device__ __forceinline__ void select_body(
       __syncthreads();
       const unsigned long long prefix = sh.prefix;
 #pragma unroll
-      for (int j = 0; j < (REG ? SEL_KPT : n_chunks); ++j) {
+      for (int j = 0; j < (REG ? KPT : n_chunks); ++j) {
         unsigned long long key;
         if (get_key(j, key)) {
           const bool match = (byte == 7) || ((key >> (8 * (byte + 1))) == (prefix >> (8 * (byte + 1))));
@@ -304,11 +305,11 @@ __device__ __forceinline__ void select_body(
     // order), and each then takes the rank of its slot as its place in the output
     if constexpr (REG) {
 #pragma unroll
-      for (int j = 0; j < SEL_KPT; ++j)
+      for (int j = 0; j < KPT; ++j)
         if (rkey[j] != KEY_NONE && rkey[j] <= cut) sh.list[atomicAdd(&sh.nlist, 1)] = j * SEL_THREADS + tid;
       __syncthreads();
 #pragma unroll
-      for (int j = 0; j < SEL_KPT; ++j) {
+      for (int j = 0; j < KPT; ++j) {
         if (rkey[j] != KEY_NONE && rkey[j] <= cut) {
           const int slot = j * SEL_THREADS + tid;
           int idx = 0;
@@ -329,7 +330,7 @@ __device__ __forceinline__ void select_body(
   }
 
 #pragma unroll
-  for (int j = 0; j < (REG ? SEL_KPT : n_chunks); ++j) {
+  for (int j = 0; j < (REG ? KPT : n_chunks); ++j) {
     if (REG && j >= n_chunks) break;
     const int slot = j * SEL_THREADS + tid;
     unsigned long long key = 0;

@@ -242,6 +242,12 @@ def test_select_bit_exact(kvr):
     run_select_case(kvr, rng, 1, 2, 200, 400, [400], 20, 30, 200, 60, 200, 50)
     say("select ragged tail, 1025 slots")
     run_select_case(kvr, rng, 1, 1, 1025, 5000, [5000], 100, 400, 1025, 2000, 1025, 0, score_levels=8)
+    say("select 9000 slots (32 keys per thread in registers), ties")
+    run_select_case(kvr, rng, 1, 2, 9000, 9100, [9050], 700, 2500, 9000, 9000, 8800, 5, score_levels=300)
+    say("select 9000 slots, a handful of evictions")
+    run_select_case(kvr, rng, 1, 1, 9000, 9100, [9050], 700, 8095, 16, 9000, 8800, 5)
+    say("select 33000 slots (keys re-read from memory in every pass), ties")
+    run_select_case(kvr, rng, 1, 1, 33000, 33100, [33000], 3000, 9000, 33000, 33000, 32500, 0, score_levels=500)
 
 
 # ----------------------------------------------------------------------------- append
