@@ -315,6 +315,37 @@ def attend_decode(q, K_ret, V_ret, ret_pos, SK, SV, params, vague_pos, n_ctx, sc
     return out, new_scores, p
 
 
+def attend_multi(q, q_pos, K_ret, V_ret, ret_pos, SK, SV, params, vague_pos, n_ctx, scale, *,
+                 scores=None, storage="f64", median_mode="midmean", sign_mask=2):
+    """Calculation phase for several query tokens at once (a chunk of prompt or
+    of drafted tokens): the cache is rebuilt once (Algorithm 4), then query t,
+    which sits at position q_pos[t], attends over the positions <= q_pos[t]
+    (a token does not see later tokens), with the G query heads of this kv head.
+    Every token's cumulative score grows by its probability summed over the
+    queries and heads.  q [Tq, G, D].  Returns (out [Tq, G, D] float64, new scores
+    float32 or None, p [Tq, G, n_ctx] with zeros at the positions a query does not
+    see)."""
+    K, V = revive(K_ret, V_ret, ret_pos, SK, SV, params, vague_pos, n_ctx,
+                  storage=storage, median_mode=median_mode, sign_mask=sign_mask)
+    q = np.asarray(q, dtype=np.float64)
+    Tq, G, D = q.shape
+    out = np.zeros((Tq, G, D))
+    p_all = np.zeros((Tq, G, n_ctx))
+    for t in range(Tq):
+        n_vis = int(q_pos[t]) + 1
+        if not (1 <= n_vis <= n_ctx):
+            raise ValueError("query position outside the context")
+        o, p = attention(q[t], K[:n_vis], V[:n_vis], scale)
+        out[t] = o
+        p_all[t, :, :n_vis] = p
+    new_scores = None
+    if scores is not None:
+        new_scores = np.array(scores, dtype=np.float32, copy=True)
+        inc = p_all.sum(axis=(0, 1))
+        new_scores[:n_ctx] = (new_scores[:n_ctx].astype(np.float64) + inc).astype(np.float32)
+    return out, new_scores, p_all
+
+
 # ---------------------------------------------------------------------------
 # one unit's whole state and one decode step
 # ---------------------------------------------------------------------------

@@ -738,3 +738,66 @@ def test_layer_budgets_preserve_the_total():
         S.layer_budgets(wl, [1.0] * (wl.layers - 1))
     with pytest.raises(ValueError):
         S.layer_budgets(wl, [8.0] + [0.01] * (wl.layers - 1))
+
+
+# ------------------------------------------------------------------ several queries at once
+def _multi_case(rng, N=40, D=128, r=3, w=4, G=2, Tq=4, n_vague=22):
+    params = rand_params(rng, r)
+    K = O.to_storage(rng.standard_normal((N, D)), "bf16")
+    V = O.to_storage(rng.standard_normal((N, D)), "bf16")
+    perm = rng.permutation(N - Tq)
+    vague = [int(p) for p in perm[:n_vague]]
+    ret = [int(p) for p in perm[n_vague:]] + list(range(N - Tq, N))      # the Tq newest tokens are retained raw
+    SK, SV = O.sketch_zeros(r, w, D)
+    SK, SV = O.insert(SK, SV, params, vague, K[vague], V[vague], storage="bf16", acc_dtype=np.float32)
+    slots = rng.permutation(len(ret) + 3)
+    ret_pos = np.full(len(ret) + 3, -1, dtype=np.int64)
+    K_ret = np.zeros((len(ret) + 3, D)); V_ret = np.zeros((len(ret) + 3, D))
+    for s_, p_ in zip(slots, ret):
+        ret_pos[s_] = p_; K_ret[s_] = K[p_]; V_ret[s_] = V[p_]
+    q = O.to_storage(rng.standard_normal((Tq, G, D)), "bf16")
+    q_pos = np.arange(N - Tq, N)
+    return params, K_ret, V_ret, ret_pos, SK, SV, vague, q, q_pos, N
+
+
+def test_attend_multi_against_library_sdpa_with_mask():
+    rng = np.random.default_rng(31)
+    params, K_ret, V_ret, ret_pos, SK, SV, vague, q, q_pos, N = _multi_case(rng)
+    scale = 1 / math.sqrt(128)
+    sc0 = rng.random(N).astype(np.float32)
+    out, sc1, p = O.attend_multi(q, q_pos, K_ret, V_ret, ret_pos, SK, SV, params, vague, N, scale,
+                                 scores=sc0, storage="bf16")
+    Kst, Vst = O.revive(K_ret, V_ret, ret_pos, SK, SV, params, vague, N, storage="bf16")
+    Tq, G, D = q.shape
+    mask = torch.as_tensor(np.arange(N)[None, :] <= q_pos[:, None])                       # [Tq, N]
+    qt = torch.as_tensor(q).permute(1, 0, 2).unsqueeze(0)                                  # [1, G, Tq, D]
+    kt = torch.as_tensor(Kst).expand(1, G, N, D)
+    vt = torch.as_tensor(Vst).expand(1, G, N, D)
+    ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, attn_mask=mask, scale=scale)
+    assert np.allclose(out, ref[0].permute(1, 0, 2).numpy(), rtol=1e-12, atol=1e-12)
+    # a query puts no probability on later positions, all of it on the visible ones
+    for t in range(Tq):
+        assert np.all(p[t, :, q_pos[t] + 1:] == 0) and np.allclose(p[t].sum(axis=1), 1.0)
+    assert abs(float((sc1.astype(np.float64) - sc0).sum()) - Tq * G) < 1e-4
+    assert np.allclose(sc1, sc0 + p.sum(axis=(0, 1)), rtol=1e-6, atol=1e-7)
+
+
+def test_attend_multi_equals_one_query_at_a_time_on_the_truncated_context():
+    rng = np.random.default_rng(32)
+    params, K_ret, V_ret, ret_pos, SK, SV, vague, q, q_pos, N = _multi_case(rng, Tq=3, G=4)
+    scale = 1 / math.sqrt(128)
+    out, _, p = O.attend_multi(q, q_pos, K_ret, V_ret, ret_pos, SK, SV, params, vague, N, scale, storage="bf16")
+    for t in range(q.shape[0]):
+        rp = ret_pos.copy()
+        rp[rp > q_pos[t]] = -1                                  # later tokens do not exist yet for this query
+        o1, _, p1 = O.attend_decode(q[t], K_ret, V_ret, rp, SK, SV, params, vague, int(q_pos[t]) + 1, scale,
+                                    storage="bf16")
+        assert np.array_equal(out[t], o1) and np.array_equal(p[t, :, :q_pos[t] + 1], p1)
+    # one query at the last position is the decode case
+    o_last, sc_last, _ = O.attend_multi(q[-1:], q_pos[-1:], K_ret, V_ret, ret_pos, SK, SV, params, vague, N, scale,
+                                        scores=np.zeros(N, dtype=np.float32), storage="bf16")
+    o_dec, sc_dec, _ = O.attend_decode(q[-1], K_ret, V_ret, ret_pos, SK, SV, params, vague, N, scale,
+                                       scores=np.zeros(N, dtype=np.float32), storage="bf16")
+    assert np.array_equal(o_last[0], o_dec) and np.array_equal(sc_last, sc_dec)
+    with pytest.raises(ValueError):
+        O.attend_multi(q, q_pos + 1, K_ret, V_ret, ret_pos, SK, SV, params, vague, N, scale, storage="bf16")
