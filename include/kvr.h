@@ -295,6 +295,36 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q,
                           float* out, float* scores, int64_t n_cap,
                           void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * The Calculation Phase for n_q query tokens per sequence at once (a chunk of
+ * prompt or of drafted tokens): as the Overview describes the phase, the layer's
+ * cache is rebuilt once (Algorithm 4; Vague tokens by Algorithm 2, written to
+ * workspace and read back once) and attention then runs over it for all queries.
+ * Query t of sequence b sits at position n_ctx[b] - n_q + t (the n_q newest
+ * tokens, already pushed into the Recent part) and attends over the tokens at
+ * positions <= its own:
+ *     p[t, hq, j] = softmax over visible j of softmax_scale * q[t, hq] . k*_j
+ *     out[t, hq]  = sum_j p[t, hq, j] v*_j
+ * and, if scores is not NULL, every token's cumulative score grows by the sum of
+ * p over the n_q queries and the G q heads of its kv head.  n_q = 1 computes what
+ * kvr_attend_decode computes (by this other route).
+ * bf16 storage only, n_q * G in {1, 2, 4, 8, 16} (G = n_q_heads / n_kv_heads),
+ * otherwise KVR_ERR_UNSUPPORTED.
+ *   q          dev [B, n_q, Hq, D] bf16, read;   n_ctx dev int32 [B], read
+ *   k_ret .. vague_cap, scores, n_cap   as for kvr_attend_decode (ret_pos must not be NULL)
+ *   out        dev float32 [B, n_q, Hq, D], written
+ *   ws         per kvr_attend_multi_workspace_size(desc, n_q, ret_cap, vague_cap): the rebuilt
+ *              Vague tokens of all units (2 * vague_cap * D * 2 bytes per unit), slice partials, logits
+ */
+int32_t kvr_attend_multi_workspace_size(const kvr_desc* desc, int32_t n_q, int64_t ret_cap, int64_t vague_cap,
+                                        size_t* bytes);
+int32_t kvr_attend_multi(const kvr_desc* desc, const void* q, int32_t n_q, const int32_t* n_ctx,
+                         const void* k_ret, const void* v_ret, const int32_t* ret_pos, int32_t ret_cap,
+                         const void* sketch_k, const void* sketch_v,
+                         const int32_t* vague_pos, const int32_t* n_vague, int32_t vague_cap,
+                         float* out, float* scores, int64_t n_cap,
+                         void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,7 +31,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvr.so")
 
 EXPORTS = ["kvr_version", "kvr_last_hip_error", "kvr_profile_events", "kvr_hash_params_from_seed", "kvr_hash_host",
            "kvr_workspace_size", "kvr_append", "kvr_select", "kvr_encode", "kvr_step_update",
-           "kvr_swap_back", "kvr_reconstruct", "kvr_attend_decode"]
+           "kvr_swap_back", "kvr_reconstruct", "kvr_attend_decode", "kvr_attend_multi_workspace_size",
+           "kvr_attend_multi"]
 
 
 class KvrError(RuntimeError):
@@ -91,6 +92,11 @@ def lib() -> C.CDLL:
         L.kvr_attend_decode.restype = i32
         L.kvr_attend_decode.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, i64,
                                         vp, sz, vp]
+        L.kvr_attend_multi_workspace_size.restype = i32
+        L.kvr_attend_multi_workspace_size.argtypes = [dp, i32, i64, i64, C.POINTER(sz)]
+        L.kvr_attend_multi.restype = i32
+        L.kvr_attend_multi.argtypes = [dp, vp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, i64,
+                                       vp, sz, vp]
         _lib = L
     return _lib
 
@@ -298,3 +304,28 @@ def kvr_attend_decode(desc, q, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_
         _ptr(out, torch.float32, desc.batch * desc.n_q_heads * D, "out"),
         _ptr(scores, torch.float32, U * n_cap, "scores", True), n_cap, wp, wb, _stream())
     _check("kvr_attend_decode", rc)
+
+
+def kvr_attend_multi_workspace_size(desc, n_q, ret_cap, vague_cap) -> int:
+    n = C.c_size_t(0)
+    _check("kvr_attend_multi_workspace_size",
+           lib().kvr_attend_multi_workspace_size(C.byref(desc), n_q, ret_cap, vague_cap, C.byref(n)))
+    return n.value
+
+
+def kvr_attend_multi(desc, q, n_q, n_ctx, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_v, vague_pos, n_vague,
+                     vague_cap, out, scores, n_cap, ws):
+    U, D, dt = desc.batch * desc.n_kv_heads, desc.head_dim, _torch_dtype(desc)
+    S = desc.r * desc.w * D
+    wp, wb = _ws(ws)
+    rc = lib().kvr_attend_multi(
+        C.byref(desc), _ptr(q, dt, desc.batch * n_q * desc.n_q_heads * D, "q"), n_q,
+        _ptr(n_ctx, torch.int32, desc.batch, "n_ctx"),
+        _ptr(k_ret, dt, U * ret_cap * D, "k_ret"), _ptr(v_ret, dt, U * ret_cap * D, "v_ret"),
+        _ptr(ret_pos, torch.int32, U * ret_cap, "ret_pos"), ret_cap,
+        _ptr(sketch_k, dt, U * S, "sketch_k", True), _ptr(sketch_v, dt, U * S, "sketch_v", True),
+        _ptr(vague_pos, torch.int32, U * vague_cap, "vague_pos", True),
+        _ptr(n_vague, torch.int32, U, "n_vague", True), vague_cap,
+        _ptr(out, torch.float32, desc.batch * n_q * desc.n_q_heads * D, "out"),
+        _ptr(scores, torch.float32, U * n_cap, "scores", True), n_cap, wp, wb, _stream())
+    _check("kvr_attend_multi", rc)

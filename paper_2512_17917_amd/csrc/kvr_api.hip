@@ -268,9 +268,71 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret
   a.part_o = (float*)(base + plan.off_part_o);
   a.part_ml = (float*)(base + plan.off_part_ml);
   a.logits = scores ? (float*)(base + plan.off_logits) : nullptr;
+  a.n_q = 1;
   const hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;
   g_ev_start = g_ev_stop = nullptr;
   return finish(kvr::launch_attend(d, desc->dtype, a, plan, (hipStream_t)stream, e0, e1));
+}
+
+static int32_t check_multi(const kvr_desc* desc, kvr::DevDesc& d, int32_t n_q) {
+  const int32_t rc = check_desc(desc, d);
+  if (rc != KVR_OK) return rc;
+  if (n_q < 1) return KVR_ERR_INVALID_ARG;
+  if (desc->dtype != KVR_BF16) return KVR_ERR_UNSUPPORTED;
+  const long long ncol = (long long)n_q * d.G;
+  if (ncol != 1 && ncol != 2 && ncol != 4 && ncol != 8 && ncol != 16) return KVR_ERR_UNSUPPORTED;
+  return KVR_OK;
+}
+
+int32_t kvr_attend_multi_workspace_size(const kvr_desc* desc, int32_t n_q, int64_t ret_cap, int64_t vague_cap,
+                                        size_t* bytes) {
+  kvr::DevDesc d;
+  const int32_t rc = check_multi(desc, d, n_q);
+  if (rc != KVR_OK) return rc;
+  if (bytes == nullptr || ret_cap < 1 || ret_cap > MAX_TOKENS || vague_cap < 0 || vague_cap > MAX_TOKENS)
+    return KVR_ERR_INVALID_ARG;
+  *bytes = kvr::attend_multi_plan(d, n_q, ret_cap, vague_cap).total_bytes;
+  return KVR_OK;
+}
+
+int32_t kvr_attend_multi(const kvr_desc* desc, const void* q, int32_t n_q, const int32_t* n_ctx,
+                         const void* k_ret, const void* v_ret, const int32_t* ret_pos, int32_t ret_cap,
+                         const void* sketch_k, const void* sketch_v, const int32_t* vague_pos,
+                         const int32_t* n_vague, int32_t vague_cap, float* out, float* scores, int64_t n_cap,
+                         void* ws, size_t ws_bytes, void* stream) {
+  kvr::DevDesc d;
+  const int32_t rc = check_multi(desc, d, n_q);
+  if (rc != KVR_OK) return rc;
+  if (!q || !n_ctx || !k_ret || !v_ret || !ret_pos || !out) return KVR_ERR_INVALID_ARG;
+  if ((vague_pos == nullptr) != (n_vague == nullptr)) return KVR_ERR_INVALID_ARG;
+  if (n_vague != nullptr && (!sketch_k || !sketch_v)) return KVR_ERR_INVALID_ARG;
+  if (ret_cap < 1 || ret_cap > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  if (n_vague == nullptr) vague_cap = 0;
+  if (vague_cap < 0 || vague_cap > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
+  if (scores != nullptr && (n_cap < 1 || n_cap > MAX_TOKENS)) return KVR_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_ret) || !aligned16(v_ret) || !aligned16(out) || !aligned16(sketch_k) ||
+      !aligned16(sketch_v))
+    return KVR_ERR_INVALID_ARG;
+  const kvr::MultiPlan plan = kvr::attend_multi_plan(d, n_q, ret_cap, vague_cap);
+  if (ws == nullptr || !aligned16(ws)) return KVR_ERR_INVALID_ARG;
+  if (ws_bytes < plan.total_bytes) return KVR_ERR_WORKSPACE_TOO_SMALL;
+  kvr::AttendArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = q;
+  a.k_ret = k_ret;
+  a.v_ret = v_ret;
+  a.ret_pos = ret_pos;
+  a.ret_cap = ret_cap;
+  a.sk = sketch_k;
+  a.sv = sketch_v;
+  a.vague_pos = vague_pos;
+  a.n_vague = n_vague;
+  a.vague_cap = vague_cap;
+  a.out = out;
+  a.scores = scores;
+  a.n_cap = n_cap;
+  a.n_q = n_q;
+  return finish(kvr::launch_attend_multi(d, a, n_ctx, n_q, plan, ws, (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -32,6 +32,8 @@ static int slice_tokens_for(long long tokens, long long units) {
   return (int)st;
 }
 
+int attend_slice_tokens(long long tokens, long long units) { return slice_tokens_for(tokens, units); }
+
 AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long vague_cap) {
   AttendPlan p;
   const long long units = (long long)d.B * d.Hkv;
@@ -408,7 +410,9 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
       if (sq == 0 && live) {
         const float tot = (sO[0][tid] + sO[1][tid]) + (sO[2][tid] + sO[3][tid]);
         const float L = sL[g];
-        a.out[((size_t)b * d.Hq + (size_t)hk * G) * D + idx] = (L > 0.f) ? tot / L : 0.f;
+        // column g of the partials = (query tq, head gh of the group); out is [B, n_q, Hq, D]
+        const int tq = g / d.G, gh = g % d.G;
+        a.out[((((size_t)b * a.n_q + tq) * d.Hq) + (size_t)hk * d.G + gh) * D + (idx % D)] = (L > 0.f) ? tot / L : 0.f;
       }
     }
   }
@@ -467,6 +471,23 @@ static void launch_main_r(const DevDesc& d, const AttendArgs& a, dim3 grid, hipS
   }
 }
 
+hipError_t launch_attend_combine(const DevDesc& d, const AttendArgs& a, int n_cols, hipStream_t st) {
+  const int units = d.B * d.Hkv;
+  const long long tot_cap = (long long)a.ret_cap + a.vague_cap;
+  int cx = (int)((tot_cap + 1023) / 1024);
+  if (cx < 1) cx = 1;
+  const dim3 grid(cx, units), block(256);
+  switch (n_cols) {
+    case 1: hipLaunchKernelGGL((attend_combine_kernel<1>), grid, block, 0, st, d, a); break;
+    case 2: hipLaunchKernelGGL((attend_combine_kernel<2>), grid, block, 0, st, d, a); break;
+    case 4: hipLaunchKernelGGL((attend_combine_kernel<4>), grid, block, 0, st, d, a); break;
+    case 8: hipLaunchKernelGGL((attend_combine_kernel<8>), grid, block, 0, st, d, a); break;
+    case 16: hipLaunchKernelGGL((attend_combine_kernel<16>), grid, block, 0, st, d, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 template <int G>
 static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, const AttendPlan& plan,
                            hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
@@ -521,11 +542,7 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
   }
   if (ev_stop) (void)hipEventRecord(ev_stop, st);
   if (e != hipSuccess) return e;
-  const long long tot_cap = (long long)a.ret_cap + a.vague_cap;
-  int cx = (int)((tot_cap + 1023) / 1024);
-  if (cx < 1) cx = 1;
-  hipLaunchKernelGGL((attend_combine_kernel<G>), dim3(cx, units), dim3(256), 0, st, d, a);
-  return hipGetLastError();
+  return launch_attend_combine(d, a, G, st);
 }
 
 hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, const AttendPlan& plan,

@@ -49,6 +49,8 @@ struct AttendArgs {
   int slice0;        // generic kernel: index of its first partial
   int n_rslices;     // staged kernel: index of its first partial
   int n_vslices;     // staged kernel: workgroups per unit
+  int n_q;           // merge kernel: query tokens per sequence (1 for kvr_attend_decode); the partials'
+                     // columns are then (query t, head g) = t * G + g and out is [B, n_q, Hq, D]
 };
 
 // Retained slots by the MFMA kernel (bf16): slices 0 .. n_rslices-1 of a.slice_tokens slots.
@@ -71,6 +73,21 @@ hipError_t launch_reconstruct(const DevDesc& d, int dtype, const void* sk, const
 // merge kernel), for profiling.
 hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, const AttendPlan& plan,
                          hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
+
+// tokens per slice when `tokens` tokens of each of `units` units are cut for about 2048 workgroups
+int attend_slice_tokens(long long tokens, long long units);
+
+// merge kernel alone: n_cols = partial columns per unit (G for one query, n_q * G for several)
+hipError_t launch_attend_combine(const DevDesc& d, const AttendArgs& a, int n_cols, hipStream_t st);
+
+// kvr_attend_multi: workspace carve-up and launch (bf16, n_q * G in {1, 2, 4, 8, 16})
+struct MultiPlan {
+  int rslice_tokens, n_rslices, vslice_tokens, n_vslices, n_slices;
+  size_t off_khat, off_vhat, off_part_o, off_part_ml, off_logits, total_bytes;
+};
+MultiPlan attend_multi_plan(const DevDesc& d, int n_q, long long ret_cap, long long vague_cap);
+hipError_t launch_attend_multi(const DevDesc& d, const AttendArgs& a, const int32_t* n_ctx, int n_q,
+                               const MultiPlan& plan, void* ws, hipStream_t st);
 
 // Staged kernel over the Vague list (bf16, values signed only, G <= 4, r in {3,4}).
 hipError_t launch_attend_vague_staged(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,

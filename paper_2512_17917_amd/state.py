@@ -64,6 +64,19 @@ class LayerState:
                               self.ws_attend)
         return self.out
 
+    def attend_multi(self, q, n_q, accumulate_scores=True, ws=None):
+        """n_q query tokens per sequence (q [B, n_q, Hq, D]) at the n_q newest
+        positions, over one rebuilt cache.  Returns out [B, n_q, Hq, D] float32."""
+        if ws is None:
+            n = kvr.kvr_attend_multi_workspace_size(self.desc, n_q, self.ret_cap, self.vague_cap)
+            ws = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
+        B, Hq, D = self.desc.batch, self.desc.n_q_heads, self.desc.head_dim
+        out = torch.zeros(B, n_q, Hq, D, dtype=torch.float32, device=self.device)
+        kvr.kvr_attend_multi(self.desc, q, n_q, self.n_ctx, self.k_ret, self.v_ret, self.ret_pos, self.ret_cap,
+                             self.sketch_k, self.sketch_v, self.vague_pos, self.n_vague, self.vague_cap, out,
+                             self.scores if accumulate_scores else None, self.n_cap, ws)
+        return out
+
     def step_update(self, k_new, v_new):
         """append + select + encode in one launch (decode steady state)."""
         kvr.kvr_step_update(self.desc, k_new, v_new, self.n_ctx, self.k_ret, self.v_ret, self.ret_pos,
