@@ -130,6 +130,10 @@ def main():
                     help="non-uniform per-layer budgets: layer l gets budget * (1 - s + 2 s l / (L - 1)), the same "
                          "total; 0 (default) = the uniform budget of the headline configuration")
     ap.add_argument("--max-swaps", type=int, default=4, help="bound of the swap loop per unit and step")
+    ap.add_argument("--multi-q", type=int, default=0,
+                    help="also time kvr_attend_multi with this many query tokens per sequence on every layer "
+                         "(queries at the newest positions of the state after the timed steps; reported beside "
+                         "the headline figure, not part of it)")
     ap.add_argument("--event-every", type=int, default=5,
                     help="record the HIP event pair around the attention kernels on every n-th launch of the timed "
                          "region (the two event records cost about 10 us per launch they bracket; 5 does not "
@@ -306,6 +310,27 @@ def main():
             "launch_sampling": f"HIP events on every {ev_every}. launch of the timed region",
         },
     }
+    if args.multi_q > 0:
+        nq = args.multi_q
+        qm = S.queries_many(wl, 0, 1, 1 + nq, device=dev).permute(1, 0, 2, 3).contiguous()    # [B, nq, Hq, D]
+        ws_bytes = max(kvr.kvr_attend_multi_workspace_size(descs[l], nq, layers[l].ret_cap, layers[l].vague_cap)
+                       for l in range(L))
+        ws_m = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        for l in range(min(L, 4)):
+            layers[l].attend_multi(qm, nq, accumulate_scores=True, ws=ws_m)
+        torch.cuda.synchronize()
+        reps = 3
+        tm0 = time.perf_counter()
+        for _ in range(reps):
+            for l in range(L):
+                layers[l].attend_multi(qm, nq, accumulate_scores=True, ws=ws_m)
+        torch.cuda.synchronize()
+        ms_layer = (time.perf_counter() - tm0) * 1e3 / (reps * L)
+        result["attend_multi"] = {"n_q": nq, "ms_per_layer": ms_layer,
+                                  "query_tokens_per_s": nq * B / (ms_layer * 1e-3 * L),
+                                  "decode_ms_per_layer_for_comparison": result["ms_per_step"] / L}
+        log(f"[bench] attend_multi n_q={nq}: {ms_layer * 1e3:.1f} us per layer")
+        del ws_m
     if args.replace_rate is not None:
         n_sw = torch.zeros(B, Hkv, dtype=torch.int32, device=dev)
         layers[0].swap_back(args.replace_rate, args.max_swaps, n_sw)       # one more loop, to report its count

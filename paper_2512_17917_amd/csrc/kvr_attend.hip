@@ -299,9 +299,12 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
       for (int g = 0; g < G; ++g) x[u][g] = -__builtin_inff();
       if (t < total) {
         const float* lg = a.logits + ((size_t)unit * tot_cap + t) * G;
-        if constexpr (G == 4) {
-          const float4 v = *reinterpret_cast<const float4*>(lg);
-          x[u][0] = v.x; x[u][1] = v.y; x[u][2] = v.z; x[u][3] = v.w;
+        if constexpr (G % 4 == 0) {
+#pragma unroll
+          for (int g4 = 0; g4 < G; g4 += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(lg + g4);
+            x[u][g4] = v.x; x[u][g4 + 1] = v.y; x[u][g4 + 2] = v.z; x[u][g4 + 3] = v.w;
+          }
         } else {
 #pragma unroll
           for (int g = 0; g < G; ++g) x[u][g] = lg[g];

@@ -19,40 +19,21 @@
 // vectors as the B operand give lane l the logits of tokens 4 (l div 16) + {0..3}
 // for column l mod 16.  Query t sits at position n_ctx - n_q + t and sees the
 // tokens at positions up to its own; what it does not see gets the logit -inf.
-// Online softmax per column; p * v in float32 on the vector ALUs with the weights
-// fetched by DPP row broadcasts.
-#include "kvr_launch.h"
+// Online softmax per column.  p * v is a second matrix product per tile,
+// out[column][channel] += P[column][token] V[token][channel], on
+// v_mfma_f32_16x16x16_bf16: the weights a lane holds (its column, its four tokens)
+// are already an A operand (split into bf16 hi + lo, 16 mantissa bits together);
+// a lane's four V pieces (its four tokens, channels 8 (l mod 16) .. +7) give, one
+// channel at a time, eight B operands after a 4 x 8 transpose in registers; the
+// instruction for channel c of the pieces leaves lane l with the sums of columns
+// 4 (l div 16) + {0..3} for channel 8 (l mod 16) + c.
+#include "kvr_staged.h"
 
 namespace kvr {
 
 typedef __bf16 bf16x8m_t __attribute__((ext_vector_type(8)));
 typedef float f32x4m_t __attribute__((ext_vector_type(4)));
 
-template <int N>
-__device__ __forceinline__ float row_bcast_m(float x) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + N, 0xf, 0xf, true));
-}
-
-template <int NCOL, int I>
-struct ColStep {
-  __device__ static __forceinline__ void fma(float (&acc)[NCOL][8], float p, const float (&v)[8]) {
-    const float pg = row_bcast_m<I>(p);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) acc[I][c] = fmaf(pg, v[c], acc[I][c]);
-    ColStep<NCOL, I + 1>::fma(acc, p, v);
-  }
-  __device__ static __forceinline__ void scale(float (&acc)[NCOL][8], float corr) {
-    const float cg = row_bcast_m<I>(corr);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) acc[I][c] *= cg;
-    ColStep<NCOL, I + 1>::scale(acc, corr);
-  }
-};
-template <int NCOL>
-struct ColStep<NCOL, NCOL> {
-  __device__ static __forceinline__ void fma(float (&)[NCOL][8], float, const float (&)[8]) {}
-  __device__ static __forceinline__ void scale(float (&)[NCOL][8], float) {}
-};
 
 // One call of the dense kernel: rows [0, cap) of k / v per unit, position of row
 // s in pos (negative: empty), rows >= n_valid[unit] (if given) do not exist.
@@ -108,11 +89,9 @@ __global__ __launch_bounds__(256) void attend_dense_multi_kernel(DevDesc d, Dens
       }
     }
     float m_run = NEG_INF, l_run = 0.f;
-    float acc[NCOL][8];
+    f32x4_t acc[8];            // acc[c][i]: column 4 r16 + i, channel 8 col + c
 #pragma unroll
-    for (int c_ = 0; c_ < NCOL; ++c_)
-#pragma unroll
-      for (int c = 0; c < 8; ++c) acc[c_][c] = 0.f;
+    for (int c = 0; c < 8; ++c) acc[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     const int n_tiles = (t_end > t_begin) ? (t_end - t_begin + 15) >> 4 : 0;
     for (int ti = wave; ti < n_tiles; ti += NW) {
@@ -157,7 +136,14 @@ __global__ __launch_bounds__(256) void attend_dense_multi_kernel(DevDesc d, Dens
       if (__any(m_new > m_run)) {
         const float corr = (m_run == NEG_INF) ? 0.f : __expf(m_run - m_new);
         l_run *= corr;
-        ColStep<NCOL, 0>::scale(acc, (m_new == NEG_INF) ? 1.f : corr);
+        // this lane's accumulators belong to columns 4 r16 + i: their factors sit in
+        // lanes 4 r16 + i of this 16-lane row
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float ci = __shfl(corr, (lane & 48) + 4 * r16 + i);
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[c][i] *= ci;
+        }
       }
       m_run = m_new;
       float p[4];
@@ -166,41 +152,50 @@ __global__ __launch_bounds__(256) void attend_dense_multi_kernel(DevDesc d, Dens
         p[i] = (s[i] == NEG_INF) ? 0.f : __expf(s[i] - m_new);
         l_run += p[i];
       }
-      const bool any_invalid = __any(invalid);
+      if (__any(invalid)) {           // an empty row may hold anything, even NaN: weight 0 is not enough
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        float v[8] = {__uint_as_float(vt[j].x << 16), __uint_as_float(vt[j].x & 0xffff0000u),
-                      __uint_as_float(vt[j].y << 16), __uint_as_float(vt[j].y & 0xffff0000u),
-                      __uint_as_float(vt[j].z << 16), __uint_as_float(vt[j].z & 0xffff0000u),
-                      __uint_as_float(vt[j].w << 16), __uint_as_float(vt[j].w & 0xffff0000u)};
-        if (any_invalid) {            // an empty row may hold anything, even NaN: weight 0 is not enough
-          const bool dead = tpos[j] < 0;
-#pragma unroll
-          for (int c = 0; c < 8; ++c) v[c] = dead ? 0.f : v[c];
-        }
-        ColStep<NCOL, 0>::fma(acc, p[j], v);
+        for (int j = 0; j < 4; ++j)
+          if (tpos[j] < 0) vt[j] = make_uint4(0u, 0u, 0u, 0u);
       }
+      // weights as A operands: bf16 hi + lo of the four tokens of this lane's column
+      uint32_t hb[4], lb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        hb[i] = __float_as_uint(p[i]) & 0xffff0000u;
+        lb[i] = __float_as_uint(p[i] - __uint_as_float(hb[i]));
+      }
+      const short4_t a_hi = pack_k4(pair_hi(hb[0], hb[1]), pair_hi(hb[2], hb[3]));
+      const short4_t a_lo = pack_k4(pair_hi(lb[0], lb[1]), pair_hi(lb[2], lb[3]));
+      // values as B operands: channel c of the four tokens' pieces
+      short4_t bop[8];
+      bop[0] = pack_k4(pair_lo(vt[0].x, vt[1].x), pair_lo(vt[2].x, vt[3].x));
+      bop[1] = pack_k4(pair_hi(vt[0].x, vt[1].x), pair_hi(vt[2].x, vt[3].x));
+      bop[2] = pack_k4(pair_lo(vt[0].y, vt[1].y), pair_lo(vt[2].y, vt[3].y));
+      bop[3] = pack_k4(pair_hi(vt[0].y, vt[1].y), pair_hi(vt[2].y, vt[3].y));
+      bop[4] = pack_k4(pair_lo(vt[0].z, vt[1].z), pair_lo(vt[2].z, vt[3].z));
+      bop[5] = pack_k4(pair_hi(vt[0].z, vt[1].z), pair_hi(vt[2].z, vt[3].z));
+      bop[6] = pack_k4(pair_lo(vt[0].w, vt[1].w), pair_lo(vt[2].w, vt[3].w));
+      bop[7] = pack_k4(pair_hi(vt[0].w, vt[1].w), pair_hi(vt[2].w, vt[3].w));
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, bop[c], acc[c], 0, 0, 0);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bop[c], acc[c], 0, 0, 0);
     }
 
-    // the four 16-lane rows of the wave hold different tokens: add them
-#pragma unroll
-    for (int c_ = 0; c_ < NCOL; ++c_)
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        acc[c_][c] += __shfl_xor(acc[c_][c], 16);
-        acc[c_][c] += __shfl_xor(acc[c_][c], 32);
-      }
+    // a lane's sums of weights cover its own four tokens of every tile: add the four 16-lane rows
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
 
     __syncthreads();             // the previous item's readers are done with the LDS arrays
-    if (r16 == 0) {
 #pragma unroll
-      for (int c_ = 0; c_ < NCOL; ++c_)
+    for (int i = 0; i < 4; ++i) {
+      const int c_ = 4 * r16 + i;
+      if (c_ < NCOL) {
 #pragma unroll
-        for (int c = 0; c < 8; ++c) s_acc[wave][c_][col * 8 + c] = acc[c_][c];
-      if (col_live) { s_m[wave][col] = m_run; s_l[wave][col] = l_run; }
+        for (int c = 0; c < 8; ++c) s_acc[wave][c_][col * 8 + c] = acc[c][i];
+      }
     }
+    if (r16 == 0 && col_live) { s_m[wave][col] = m_run; s_l[wave][col] = l_run; }
     __syncthreads();
     const size_t part = (size_t)unit * a.n_slices + a.slice0 + slice;
     float* po = a.part_o + part * NCOL * D;

@@ -29,6 +29,58 @@ __global__ __launch_bounds__(256) void reconstruct_kernel(DevDesc d, const T* __
   Store<T>::store16(v_out + o, vf);
 }
 
+// bf16 storage, three rows: the median of three is one of its inputs, so nothing
+// has to be rounded; rows are flipped on their packed bits, widened to float32
+// for the comparison (exact) and the winner's upper half is stored.
+__device__ __forceinline__ uint32_t med3_pair_bf16(uint32_t a, uint32_t b, uint32_t c) {
+  const float lo = __builtin_amdgcn_fmed3f(__uint_as_float(a << 16), __uint_as_float(b << 16), __uint_as_float(c << 16));
+  const float hi = __builtin_amdgcn_fmed3f(__uint_as_float(a & 0xffff0000u), __uint_as_float(b & 0xffff0000u),
+                                           __uint_as_float(c & 0xffff0000u));
+  return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+
+__device__ __forceinline__ uint4 query_piece3(const DevDesc& d, const bf16_t* __restrict__ sx, const int (&h)[3],
+                                              const uint32_t (&flip)[3], int c0) {
+  uint4 r[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    r[i] = *reinterpret_cast<const uint4*>(sx + ((size_t)i * d.w + h[i]) * D + c0);
+    r[i].x ^= flip[i]; r[i].y ^= flip[i]; r[i].z ^= flip[i]; r[i].w ^= flip[i];
+  }
+  return make_uint4(med3_pair_bf16(r[0].x, r[1].x, r[2].x), med3_pair_bf16(r[0].y, r[1].y, r[2].y),
+                    med3_pair_bf16(r[0].z, r[1].z, r[2].z), med3_pair_bf16(r[0].w, r[1].w, r[2].w));
+}
+
+__global__ __launch_bounds__(256) void reconstruct3_bf16_kernel(DevDesc d, const bf16_t* __restrict__ sk,
+                                                                const bf16_t* __restrict__ sv,
+                                                                const int32_t* __restrict__ tok_pos,
+                                                                const int32_t* __restrict__ count, int cap,
+                                                                bf16_t* __restrict__ k_out,
+                                                                bf16_t* __restrict__ v_out) {
+  constexpr int LPT = 16, TPB = 256 / LPT;
+  const int unit = blockIdx.y;
+  const int n = clampi(count[unit], 0, cap);
+  const int t = blockIdx.x * TPB + threadIdx.x / LPT;
+  if (t >= n) return;
+  const int c0 = (threadIdx.x % LPT) * 8;
+  const int J = tok_pos[(size_t)unit * cap + t];
+  const size_t sk_unit = (size_t)unit * 3 * d.w * D;
+  int h[3];
+  uint32_t fk[3], fv[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    h[i] = bucket_of(d, i, J);
+    const uint32_t neg = sign_neg(d, i, J) ? 0x80008000u : 0u;
+    fk[i] = (d.sign_mask & 1) ? neg : 0u;
+    fv[i] = (d.sign_mask & 2) ? neg : 0u;
+  }
+  const uint4 kq = query_piece3(d, sk + sk_unit, h, fk, c0);
+  const uint4 vq = query_piece3(d, sv + sk_unit, h, fv, c0);
+  const size_t o = ((size_t)unit * cap + t) * D + c0;
+  *reinterpret_cast<uint4*>(k_out + o) = kq;
+  *reinterpret_cast<uint4*>(v_out + o) = vq;
+}
+
 template <typename T>
 static hipError_t launch_t(const DevDesc& d, const void* sk, const void* sv, const int32_t* tok_pos,
                            const int32_t* count, int cap, void* k_out, void* v_out, hipStream_t st) {
@@ -51,6 +103,11 @@ hipError_t launch_reconstruct(const DevDesc& d, int dtype, const void* sk, const
                               const int32_t* tok_pos, const int32_t* count, int cap, void* k_out,
                               void* v_out, hipStream_t st) {
   if (cap <= 0) return hipSuccess;
+  if (dtype == KVR_BF16 && d.r == 3) {
+    hipLaunchKernelGGL(reconstruct3_bf16_kernel, dim3((cap + 15) / 16, d.B * d.Hkv), dim3(256), 0, st, d,
+                       (const bf16_t*)sk, (const bf16_t*)sv, tok_pos, count, cap, (bf16_t*)k_out, (bf16_t*)v_out);
+    return hipGetLastError();
+  }
   if (dtype == KVR_F32) return launch_t<float>(d, sk, sv, tok_pos, count, cap, k_out, v_out, st);
   return launch_t<bf16_t>(d, sk, sv, tok_pos, count, cap, k_out, v_out, st);
 }
