@@ -5,11 +5,13 @@
 // rebuilt cache; with n_q queries per sequence the rebuild is shared by all of
 // them, which is the point of batching them.
 //
-//   1. kvr_reconstruct's kernel writes the rebuilt Vague tokens to workspace
-//      (one layer's worth; they are read back once by step 3);
-//   2. the dense kernel below runs over the retained slots,
-//   3. and again over the rebuilt tokens (same kernel, other arrays),
-//   4. the merge kernel of kvr_attend_decode combines the slice partials, writes
+//   1. the dense kernel below runs over the retained slots,
+//   2. and again over the Vague index list: with three sketch rows it rebuilds each
+//      16-token tile itself (sketch rows gathered from L2, median by selection; a
+//      rebuilt piece serves all columns and never reaches memory); otherwise
+//      kvr_reconstruct's kernel first writes the rebuilt tokens to workspace (one
+//      layer's worth) and the dense kernel reads them like retained rows,
+//   3. the merge kernel of kvr_attend_decode combines the slice partials, writes
 //      `out` and adds the probabilities to the cumulative scores.
 //
 // The dense kernel is the retained-slot kernel of kvr_attend_decode with the
@@ -46,6 +48,8 @@ struct DenseArgs {
   const int32_t* pos;       // [units, cap]
   const int32_t* n_valid;   // [units] or null
   int cap;
+  const bf16_t* sk;         // sketch mode: k and v are not read; the rows are rebuilt from the unit's
+  const bf16_t* sv;         // sketches [units, 3, w, D] by Algorithm 2, tile by tile (three rows only)
   int slice_tokens, n_slices_here;
   int slice0, n_slices;     // partial index of this call's first slice / partials per unit
   int tok0, tot_cap;        // logits index of row 0 / logits rows per unit
@@ -54,7 +58,7 @@ struct DenseArgs {
   float* logits;            // [units, tot_cap, NCOL] or null
 };
 
-template <int NCOL>
+template <int NCOL, bool SKETCH>
 __global__ __launch_bounds__(256) void attend_dense_multi_kernel(DevDesc d, DenseArgs a) {
   constexpr int NW = 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -99,15 +103,53 @@ __global__ __launch_bounds__(256) void attend_dense_multi_kernel(DevDesc d, Dens
       // K: token t0 + col, channels 32 kx + 8 r16 .. +7;  V: token t0 + 4 r16 + j, channels 8 col .. +7
       uint4 ka[4], vt[4];
       int tpos[4];
-      const int tk = min(t0 + col, a.cap - 1);
+      if constexpr (SKETCH) {
+        // Lane (r16, col) hashes token t0 + col once: its three slots (16 bits each) and the
+        // rows' signs for keys (bits 16..18 of y) and values (bits 19..21).  The K operand is
+        // that token's; the V pieces belong to tokens t0 + 4 r16 + j, whose records sit in
+        // lanes 4 r16 + j of this 16-lane row.
+        const int tk = t0 + col;
+        const int J = (tk < t_end) ? pp[min(tk, a.cap - 1)] : -1;
+        uint32_t rx, ry;
+        {
+          const uint32_t h0 = (uint32_t)bucket_of(d, 0, J), h1 = (uint32_t)bucket_of(d, 1, J),
+                         h2 = (uint32_t)bucket_of(d, 2, J);
+          uint32_t sg = 0;
 #pragma unroll
-      for (int kx = 0; kx < 4; ++kx) ka[kx] = *reinterpret_cast<const uint4*>(kk + (size_t)tk * D + 32 * kx + 8 * r16);
+          for (int i = 0; i < 3; ++i) sg |= sign_neg(d, i, J) ? (1u << i) : 0u;
+          rx = h0 | (h1 << 16);
+          ry = h2 | (((d.sign_mask & 1) ? sg : 0u) << 16) | (((d.sign_mask & 2) ? sg : 0u) << 19);
+        }
+        const bf16_t* skk = a.sk + (size_t)unit * 3 * d.w * D;
+        const bf16_t* svv = a.sv + (size_t)unit * 3 * d.w * D;
+        {
+          const int h[3] = {(int)(rx & 0xffffu), (int)(rx >> 16), (int)(ry & 0xffffu)};
+          const uint32_t fl[3] = {(ry >> 16) & 1u ? 0x80008000u : 0u, (ry >> 17) & 1u ? 0x80008000u : 0u,
+                                  (ry >> 18) & 1u ? 0x80008000u : 0u};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int tt = t0 + 4 * r16 + j;
-        const int tc = min(tt, a.cap - 1);
-        vt[j] = *reinterpret_cast<const uint4*>(vv + (size_t)tc * D + 8 * col);
-        tpos[j] = (tt < t_end) ? pp[tc] : -1;
+          for (int kx = 0; kx < 4; ++kx) ka[kx] = query_piece3(d, skk, h, fl, 32 * kx + 8 * r16);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int src = (lane & 48) + 4 * r16 + j;
+          const uint32_t vx = (uint32_t)__shfl((int)rx, src), vy = (uint32_t)__shfl((int)ry, src);
+          tpos[j] = __shfl(J, src);
+          const int h[3] = {(int)(vx & 0xffffu), (int)(vx >> 16), (int)(vy & 0xffffu)};
+          const uint32_t fl[3] = {(vy >> 19) & 1u ? 0x80008000u : 0u, (vy >> 20) & 1u ? 0x80008000u : 0u,
+                                  (vy >> 21) & 1u ? 0x80008000u : 0u};
+          vt[j] = query_piece3(d, svv, h, fl, 8 * col);
+        }
+      } else {
+        const int tk = min(t0 + col, a.cap - 1);
+#pragma unroll
+        for (int kx = 0; kx < 4; ++kx) ka[kx] = *reinterpret_cast<const uint4*>(kk + (size_t)tk * D + 32 * kx + 8 * r16);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int tt = t0 + 4 * r16 + j;
+          const int tc = min(tt, a.cap - 1);
+          vt[j] = *reinterpret_cast<const uint4*>(vv + (size_t)tc * D + 8 * col);
+          tpos[j] = (tt < t_end) ? pp[tc] : -1;
+        }
       }
       f32x4m_t S = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -222,7 +264,10 @@ template <int NCOL>
 static hipError_t launch_dense(const DevDesc& d, const DenseArgs& a, hipStream_t st) {
   const int n_wgs = d.B * d.Hkv * a.n_slices_here;
   if (n_wgs < 1) return hipSuccess;
-  hipLaunchKernelGGL(attend_dense_multi_kernel<NCOL>, dim3(n_wgs), dim3(256), 0, st, d, a);
+  if (a.sk != nullptr)
+    hipLaunchKernelGGL((attend_dense_multi_kernel<NCOL, true>), dim3(n_wgs), dim3(256), 0, st, d, a);
+  else
+    hipLaunchKernelGGL((attend_dense_multi_kernel<NCOL, false>), dim3(n_wgs), dim3(256), 0, st, d, a);
   return hipGetLastError();
 }
 
@@ -259,7 +304,11 @@ static hipError_t launch_multi_n(const DevDesc& d, const AttendArgs& a0, const i
   bf16_t* khat = (bf16_t*)(base + plan.off_khat);
   bf16_t* vhat = (bf16_t*)(base + plan.off_vhat);
   hipError_t e = hipSuccess;
-  if (a0.vague_cap > 0) {
+  // three sketch rows: the dense kernel rebuilds the Vague tokens itself, tile by tile (each
+  // rebuilt piece serves all columns of the tile and never reaches memory); otherwise
+  // they go through the workspace
+  const bool in_kernel = d.r == 3 && d.w <= 65535;
+  if (a0.vague_cap > 0 && !in_kernel) {
     e = launch_reconstruct(d, KVR_BF16, a0.sk, a0.sv, a0.vague_pos, a0.n_vague, a0.vague_cap, khat, vhat, st);
     if (e != hipSuccess) return e;
   }
@@ -275,6 +324,7 @@ static hipError_t launch_multi_n(const DevDesc& d, const AttendArgs& a0, const i
   // retained slots
   da.k = (const bf16_t*)a0.k_ret;
   da.v = (const bf16_t*)a0.v_ret;
+  da.sk = da.sv = nullptr;
   da.pos = a0.ret_pos;
   da.n_valid = nullptr;
   da.cap = a0.ret_cap;
@@ -288,6 +338,10 @@ static hipError_t launch_multi_n(const DevDesc& d, const AttendArgs& a0, const i
   if (a0.vague_cap > 0) {
     da.k = khat;
     da.v = vhat;
+    if (in_kernel) {
+      da.sk = (const bf16_t*)a0.sk;
+      da.sv = (const bf16_t*)a0.sv;
+    }
     da.pos = a0.vague_pos;
     da.n_valid = a0.n_vague;
     da.cap = a0.vague_cap;

@@ -29,28 +29,6 @@ __global__ __launch_bounds__(256) void reconstruct_kernel(DevDesc d, const T* __
   Store<T>::store16(v_out + o, vf);
 }
 
-// bf16 storage, three rows: the median of three is one of its inputs, so nothing
-// has to be rounded; rows are flipped on their packed bits, widened to float32
-// for the comparison (exact) and the winner's upper half is stored.
-__device__ __forceinline__ uint32_t med3_pair_bf16(uint32_t a, uint32_t b, uint32_t c) {
-  const float lo = __builtin_amdgcn_fmed3f(__uint_as_float(a << 16), __uint_as_float(b << 16), __uint_as_float(c << 16));
-  const float hi = __builtin_amdgcn_fmed3f(__uint_as_float(a & 0xffff0000u), __uint_as_float(b & 0xffff0000u),
-                                           __uint_as_float(c & 0xffff0000u));
-  return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
-}
-
-__device__ __forceinline__ uint4 query_piece3(const DevDesc& d, const bf16_t* __restrict__ sx, const int (&h)[3],
-                                              const uint32_t (&flip)[3], int c0) {
-  uint4 r[3];
-#pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    r[i] = *reinterpret_cast<const uint4*>(sx + ((size_t)i * d.w + h[i]) * D + c0);
-    r[i].x ^= flip[i]; r[i].y ^= flip[i]; r[i].z ^= flip[i]; r[i].w ^= flip[i];
-  }
-  return make_uint4(med3_pair_bf16(r[0].x, r[1].x, r[2].x), med3_pair_bf16(r[0].y, r[1].y, r[2].y),
-                    med3_pair_bf16(r[0].z, r[1].z, r[2].z), med3_pair_bf16(r[0].w, r[1].w, r[2].w));
-}
-
 __global__ __launch_bounds__(256) void reconstruct3_bf16_kernel(DevDesc d, const bf16_t* __restrict__ sk,
                                                                 const bf16_t* __restrict__ sv,
                                                                 const int32_t* __restrict__ tok_pos,
