@@ -168,15 +168,18 @@ __global__ __launch_bounds__(SORT_MAX_SEGS * WAVE) void encode_sort_kernel(
       rec = src_slot[(size_t)unit * cap + e];
       if (sign_neg(d, row, tok_pos[(size_t)unit * cap + e])) rec |= (int)0x80000000u;
     }
-    int lower = 0;
-    bool higher = false;
-#pragma unroll 8
-    for (int j = 0; j < WAVE; ++j) {
-      const int sj = __shfl(s, j);
-      const bool same = (sj == s);
-      lower += (same && j < lane) ? 1 : 0;
-      higher = higher || (same && j > lane);
+    // lanes with the same slot: one ballot per bit of the slot number (13 bits cover
+    // the largest w of this path; -1 = no token gets a bit pattern of its own)
+    unsigned long long same = ~0ull;
+    const unsigned su = (unsigned)s & 0x3fffu;
+#pragma unroll
+    for (int bit = 0; bit < 14; ++bit) {
+      const bool one = (su >> bit) & 1u;
+      const unsigned long long bal = __ballot(one);
+      same &= one ? bal : ~bal;
     }
+    const int lower = __popcll(same & ((1ull << lane) - 1ull));
+    const bool higher = (lane < WAVE - 1) && ((same >> (lane + 1)) != 0ull);
     if (s >= 0) {
       const int dst = cur[s] + lower;
       order[dst] = rec;
