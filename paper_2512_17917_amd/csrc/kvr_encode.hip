@@ -229,18 +229,27 @@ __global__ __launch_bounds__(256) void encode_accum_kernel(
     }
     const unsigned long long negs = __ballot(my_neg);
     const int n = min(WAVE, hi - p0);
-#pragma unroll 16
-    for (int j = 0; j < n; ++j) {
-      const int slot = __shfl(my_slot, j);
-      const bool neg = (negs >> j) & 1ull;
-      const size_t src = ((size_t)unit * src_rows + slot) * D + 2 * lane;
-      float k0, k1, v0, v1;
-      load_pair(k_src + src, k0, k1);
-      load_pair(v_src + src, v0, v1);
-      ak0 += (fk && neg) ? -k0 : k0;
-      ak1 += (fk && neg) ? -k1 : k1;
-      av0 += (fv && neg) ? -v0 : v0;
-      av1 += (fv && neg) ? -v1 : v1;
+    // eight tokens' rows are requested together, then added in list order
+    constexpr int NB = 8;
+    for (int j0 = 0; j0 < n; j0 += NB) {
+      float k0[NB], k1[NB], v0[NB], v1[NB];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int slot = __shfl(my_slot, min(j0 + u, n - 1));
+        const size_t src = ((size_t)unit * src_rows + slot) * D + 2 * lane;
+        load_pair(k_src + src, k0[u], k1[u]);
+        load_pair(v_src + src, v0[u], v1[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        if (j0 + u < n) {
+          const bool neg = (negs >> (j0 + u)) & 1ull;
+          ak0 += (fk && neg) ? -k0[u] : k0[u];
+          ak1 += (fk && neg) ? -k1[u] : k1[u];
+          av0 += (fv && neg) ? -v0[u] : v0[u];
+          av1 += (fv && neg) ? -v1[u] : v1[u];
+        }
+      }
     }
   }
   Store<T>::store1(sk + idx, ak0);
