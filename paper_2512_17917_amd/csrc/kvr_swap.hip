@@ -48,7 +48,8 @@ struct SwapShared {
   unsigned long long vkey[SWP_LIST + 1], ckey[SWP_LIST + 1];   // sorted: vkey descending, ckey ascending
   int vidx[SWP_LIST + 1], cslot[SWP_LIST + 1];                 // Vague list index / retained slot of each entry
   int nvl, ncl;                                                // entries in use
-  int go, v_idx, v_pos, c_slot, c_pos;                         // the pair of the current round (go = 0: stop)
+  int go;                                                      // swaps decided for this scan
+  int dec[SWP_LIST][4];                                        // per swap: Vague position, Candidate position, list index, slot
 };
 
 // key of (score, position): larger = higher score, then earlier position.  -0 ranks as +0.
@@ -194,44 +195,48 @@ __global__ __launch_bounds__(SWP_THREADS) void swap_back_kernel(
     const int m = min(max_swaps - done, SWP_LIST);
     swap_build_lists<REG>(sh, vp, rp, sc, nv, ret_cap, recent_from, n_cap, m);
 
-    // ---- up to m swaps on the lists ----------------------------------------------------
-    int swaps_here = 0;
-    bool stop = false;
-    for (int k = 0; k < m; ++k) {
-      if (tid == 0) {
-        int go = 0;
-        if (sh.nvl > 0 && sh.ncl > 0) {
-          const unsigned long long kv = sh.vkey[0], kc = sh.ckey[0];
-          const float lhs = key_score(kc) * replace_rate;                 // float32 product, float32 compare
-          if (lhs < key_score(kv)) {
-            go = 1;
-            const int v_idx = sh.vidx[0], c_slot = sh.cslot[0];
-            sh.v_idx = v_idx;
-            sh.c_slot = c_slot;
-            sh.v_pos = (int)(~(uint32_t)kv);
-            sh.c_pos = (int)(~(uint32_t)kc);
-            // pop both heads; the Candidate's key enters the Vague list (at the Vague token's list
-            // index), the Vague token's key enters the Candidate list (in the Candidate's slot)
-            int n = sh.nvl - 1, at = 0;
-            for (int i = 0; i < n; ++i) { sh.vkey[i] = sh.vkey[i + 1]; sh.vidx[i] = sh.vidx[i + 1]; }
-            while (at < n && sh.vkey[at] > kc) ++at;
-            for (int i = n; i > at; --i) { sh.vkey[i] = sh.vkey[i - 1]; sh.vidx[i] = sh.vidx[i - 1]; }
-            sh.vkey[at] = kc;
-            sh.vidx[at] = v_idx;
-            n = sh.ncl - 1;
-            at = 0;
-            for (int i = 0; i < n; ++i) { sh.ckey[i] = sh.ckey[i + 1]; sh.cslot[i] = sh.cslot[i + 1]; }
-            while (at < n && sh.ckey[at] < kv) ++at;
-            for (int i = n; i > at; --i) { sh.ckey[i] = sh.ckey[i - 1]; sh.cslot[i] = sh.cslot[i - 1]; }
-            sh.ckey[at] = kv;
-            sh.cslot[at] = c_slot;
-          }
-        }
-        sh.go = go;
+    // ---- up to m swaps on the lists.  Which tokens change places depends on scores and
+    //      positions only, not on sketch contents: thread 0 decides all swaps of this scan
+    //      first and leaves the pairs in LDS, then the channel threads carry them out one
+    //      after the other without a barrier in between (a later swap that touches a slot
+    //      or a retained row of an earlier one is ordered by the thread's own program
+    //      order: a channel is only ever touched by its own thread). -------------------------
+    if (tid == 0) {
+      int n_dec = 0;
+      for (int k = 0; k < m; ++k) {
+        if (sh.nvl <= 0 || sh.ncl <= 0) break;
+        const unsigned long long kv = sh.vkey[0], kc = sh.ckey[0];
+        const float lhs = key_score(kc) * replace_rate;                   // float32 product, float32 compare
+        if (!(lhs < key_score(kv))) break;
+        const int v_idx = sh.vidx[0], c_slot = sh.cslot[0];
+        sh.dec[n_dec][0] = (int)(~(uint32_t)kv);
+        sh.dec[n_dec][1] = (int)(~(uint32_t)kc);
+        sh.dec[n_dec][2] = v_idx;
+        sh.dec[n_dec][3] = c_slot;
+        ++n_dec;
+        // pop both heads; the Candidate's key enters the Vague list (at the Vague token's list
+        // index), the Vague token's key enters the Candidate list (in the Candidate's slot)
+        int n = sh.nvl - 1, at = 0;
+        for (int i = 0; i < n; ++i) { sh.vkey[i] = sh.vkey[i + 1]; sh.vidx[i] = sh.vidx[i + 1]; }
+        while (at < n && sh.vkey[at] > kc) ++at;
+        for (int i = n; i > at; --i) { sh.vkey[i] = sh.vkey[i - 1]; sh.vidx[i] = sh.vidx[i - 1]; }
+        sh.vkey[at] = kc;
+        sh.vidx[at] = v_idx;
+        n = sh.ncl - 1;
+        at = 0;
+        for (int i = 0; i < n; ++i) { sh.ckey[i] = sh.ckey[i + 1]; sh.cslot[i] = sh.cslot[i + 1]; }
+        while (at < n && sh.ckey[at] < kv) ++at;
+        for (int i = n; i > at; --i) { sh.ckey[i] = sh.ckey[i - 1]; sh.cslot[i] = sh.cslot[i - 1]; }
+        sh.ckey[at] = kv;
+        sh.cslot[at] = c_slot;
       }
-      __syncthreads();
-      if (!sh.go) { stop = true; break; }                                   // uniform
-      const int J = sh.v_pos, pc = sh.c_pos, v_idx = sh.v_idx, c_slot = sh.c_slot;
+      sh.go = n_dec;
+    }
+    __syncthreads();
+    const int swaps_here = sh.go;
+    const bool stop = swaps_here < m;                                       // the loop condition failed (uniform)
+    for (int k = 0; k < swaps_here; ++k) {
+      const int J = sh.dec[k][0], pc = sh.dec[k][1], v_idx = sh.dec[k][2], c_slot = sh.dec[k][3];
       if (tid < 2 * D) {
         const bool is_v = tid >= D;
         const int c = is_v ? tid - D : tid;
@@ -279,13 +284,12 @@ __global__ __launch_bounds__(SWP_THREADS) void swap_back_kernel(
         rp[c_slot] = J;
         vp[v_idx] = pc;
         if (swap_log) {
-          swap_log[((size_t)unit * max_swaps + done + swaps_here) * 2] = J;
-          swap_log[((size_t)unit * max_swaps + done + swaps_here) * 2 + 1] = pc;
+          swap_log[((size_t)unit * max_swaps + done + k) * 2] = J;
+          swap_log[((size_t)unit * max_swaps + done + k) * 2 + 1] = pc;
         }
       }
-      ++swaps_here;
-      __syncthreads();           // sh.go / the pair may be overwritten; positions visible to a later scan
     }
+    __syncthreads();             // sh.go / the pairs may be overwritten; positions visible to a later scan
     done += swaps_here;
     if (stop) break;
   }
