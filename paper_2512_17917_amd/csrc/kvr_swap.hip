@@ -120,27 +120,43 @@ __device__ __noinline__ void swap_build_lists(SwapShared& sh, const int32_t* vp,
 #pragma unroll
     for (int j = 0; j < SWP_KC; ++j) ck[j] = pc[j] >= 0 ? swap_key(sc_[j], pc[j]) : SWP_NONE_MIN;
   }
+  // A thread offers the best key it still has; only the thread whose key was taken
+  // looks for its next one (the taken keys are exactly those beyond the last extreme).
   unsigned long long vprev = SWP_NONE_MIN, cprev = SWP_NONE_MAX;       // previous extremes (exclusive bounds)
   int n_vl = 0, n_cl = 0;
+  unsigned long long kmax = SWP_NONE_MAX, kmin = SWP_NONE_MIN;
+  int imax = -1, smin = -1;
+  bool redo_v = true, redo_c = true;
   for (int k = 0; k < m; ++k) {
-    unsigned long long kmax = SWP_NONE_MAX, kmin = SWP_NONE_MIN;
-    int imax = -1, smin = -1;
-    if constexpr (REG) {
+    if (redo_v) {
+      kmax = SWP_NONE_MAX;
+      imax = -1;
+      if constexpr (REG) {
 #pragma unroll
-      for (int j = 0; j < SWP_KV; ++j)
-        if (vk[j] < vprev && vk[j] > kmax) { kmax = vk[j]; imax = j * SWP_THREADS + tid; }
+        for (int j = 0; j < SWP_KV; ++j)
+          if (vk[j] < vprev && vk[j] > kmax) { kmax = vk[j]; imax = j * SWP_THREADS + tid; }
+      } else {
+        for (int i = tid; i < nv; i += SWP_THREADS) {
+          const unsigned long long key = vague_key_at(vp, sc, i, nv, n_cap);
+          if (key < vprev && key > kmax) { kmax = key; imax = i; }
+        }
+      }
+      redo_v = false;
+    }
+    if (redo_c) {
+      kmin = SWP_NONE_MIN;
+      smin = -1;
+      if constexpr (REG) {
 #pragma unroll
-      for (int j = 0; j < SWP_KC; ++j)
-        if (ck[j] > cprev && ck[j] < kmin) { kmin = ck[j]; smin = j * SWP_THREADS + tid; }
-    } else {
-      for (int i = tid; i < nv; i += SWP_THREADS) {
-        const unsigned long long key = vague_key_at(vp, sc, i, nv, n_cap);
-        if (key < vprev && key > kmax) { kmax = key; imax = i; }
+        for (int j = 0; j < SWP_KC; ++j)
+          if (ck[j] > cprev && ck[j] < kmin) { kmin = ck[j]; smin = j * SWP_THREADS + tid; }
+      } else {
+        for (int s_ = tid; s_ < ret_cap; s_ += SWP_THREADS) {
+          const unsigned long long key = cand_key_at(rp, sc, s_, ret_cap, recent_from, n_cap);
+          if (key > cprev && key < kmin) { kmin = key; smin = s_; }
+        }
       }
-      for (int s_ = tid; s_ < ret_cap; s_ += SWP_THREADS) {
-        const unsigned long long key = cand_key_at(rp, sc, s_, ret_cap, recent_from, n_cap);
-        if (key > cprev && key < kmin) { kmin = key; smin = s_; }
-      }
+      redo_c = false;
     }
     unsigned long long wmx = kmax, wmn = kmin;
 #pragma unroll
@@ -159,12 +175,12 @@ __device__ __noinline__ void swap_build_lists(SwapShared& sh, const int32_t* vp,
     }
     // keys are distinct: each extreme has exactly one owner
     if (gmax != SWP_NONE_MAX) {
-      if (kmax == gmax) { sh.vkey[n_vl] = gmax; sh.vidx[n_vl] = imax; }
+      if (kmax == gmax) { sh.vkey[n_vl] = gmax; sh.vidx[n_vl] = imax; redo_v = true; }
       ++n_vl;
       vprev = gmax;
     }
     if (gmin != SWP_NONE_MIN) {
-      if (kmin == gmin) { sh.ckey[n_cl] = gmin; sh.cslot[n_cl] = smin; }
+      if (kmin == gmin) { sh.ckey[n_cl] = gmin; sh.cslot[n_cl] = smin; redo_c = true; }
       ++n_cl;
       cprev = gmin;
     }
