@@ -8,9 +8,17 @@
  *   - Vague Sketch, Algorithm 2 (V.Query)    -> kvr_reconstruct
  *   - Recent and Candidate, Algorithm 3 (Compress: which tokens leave the
  *     Candidate part for the sketch)         -> kvr_select
+ *   - Recent and Candidate, Algorithm 3, first line (R.Push of the new token)
+ *                                            -> kvr_append
+ *   - the three of a decode step in one launch -> kvr_step_update
+ *   - Algorithm 3, second loop (a Vague token swaps places with the weakest
+ *     Candidate: V.Max_Score, V.Query, V.Delete, V.Insert(C.Top_Pop()), C.Push)
+ *                                            -> kvr_swap_back
  *   - Algorithm 4 (rebuild the KV cache) followed by self-attention and the
  *     accumulation of Softmax(QK^T) per token (Overview, Calculation Phase)
  *                                            -> kvr_attend_decode
+ *   - the same for several query tokens per sequence over one rebuilt cache
+ *                                            -> kvr_attend_multi
  *
  * Vocabulary.  A *unit* is one (sequence b, kv head h) of one attention layer;
  * unit index u = b * n_kv_heads + h.  One call works on all units of one layer.
