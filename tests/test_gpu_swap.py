@@ -48,7 +48,7 @@ def doctor_scores(states, rng):
         st.scores[low] = st.scores[low[0]]                    # three-way tie for the Candidate minimum
 
 
-def run_swap_case(kvr, LayerState, wl, layer, rate, max_swaps, rng, sign_mask=2, median_mode=0):
+def run_swap_case(kvr, LayerState, wl, layer, rate, max_swaps, rng, sign_mask=2, median_mode=0, vague_cap=None):
     units = [(b, h) for b in range(wl.batch) for h in range(wl.n_kv_heads)]
     states = U.oracle_units_from_workload(wl, layer, units, extra_tokens=4)
     for st in states:
@@ -67,7 +67,7 @@ def run_swap_case(kvr, LayerState, wl, layer, rate, max_swaps, rng, sign_mask=2,
     d = kvr.make_desc(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.r, wl.w, wl.torch_dtype,
                       hash_params=states[0].params, sign_mask=sign_mask, median_mode=median_mode)
     ls = U.layer_state_from_oracle(kvr, LayerState, d, states, wl.batch, wl.n_kv_heads,
-                                   vague_cap=wl.n_vague0 + 4)
+                                   vague_cap=vague_cap or wl.n_vague0 + 4)
     n_sw = torch.full((wl.batch, wl.n_kv_heads), -7, dtype=torch.int32, device="cuda")
     log = torch.full((wl.batch, wl.n_kv_heads, max(max_swaps, 1), 2), -1, dtype=torch.int32, device="cuda")
     ls.swap_back(rate, max_swaps, n_sw, log)
@@ -99,6 +99,33 @@ def test_swap_back_bf16_r3(kvr, LayerState, max_swaps):
         assert list(n_sw[1:]) == [1, 1, 1]
     if max_swaps == 16:
         assert total >= 9 and len(set(n_sw.tolist())) >= 3       # units did different numbers of swaps
+
+
+def test_swap_back_keys_from_memory_and_more_swaps_than_one_scan(kvr, LayerState):
+    """A Vague list capacity beyond what the kernel keeps in registers (26 keys per
+    thread) takes the path that re-reads keys from memory; 40 allowed swaps need
+    more than one scan (a scan serves 16)."""
+    say("swap, memory path / several scans")
+    rng = np.random.default_rng(8)
+    wl = S.small_workload("swpm", batch=1, n_q_heads=4, n_kv_heads=2, context=1200, budget=0.25, r=3, steps=2,
+                          cfg_id=87)
+    total, _ = run_swap_case(kvr, LayerState, wl, 0, 1.1, 8, rng, vague_cap=27000)
+    assert total >= 2
+
+    def many(states, rng_):
+        for st in states:
+            cand = [int(p) for p in st.ret_pos if 0 <= p < st.n_ctx - st.n_recent]
+            top = float(max(st.scores[cand]))
+            for n, i in enumerate(rng_.choice(len(st.vague_pos), size=30, replace=False)):
+                st.scores[st.vague_pos[i]] = np.float32(top * (2.0 + n))
+    global doctor_scores
+    saved = doctor_scores
+    doctor_scores = many
+    try:
+        total, n_sw = run_swap_case(kvr, LayerState, wl, 0, 1.1, 40, rng)
+    finally:
+        doctor_scores = saved
+    assert n_sw.min() >= 30 and n_sw.max() <= 40
 
 
 def test_swap_back_f32_and_even_rows_and_signed_keys(kvr, LayerState):
