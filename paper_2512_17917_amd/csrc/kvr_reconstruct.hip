@@ -1,7 +1,7 @@
 // kvr_reconstruct: batched V.Query (Vague Sketch, Algorithm 2).
 // One token per lane group; each lane owns a 16-byte channel chunk, gathers the
 // r sketch rows of its token for K and for V, and writes the per-channel median.
-#include "kvr_launch.h"
+#include "kvr_staged.h"
 
 namespace kvr {
 
@@ -29,12 +29,17 @@ __global__ __launch_bounds__(256) void reconstruct_kernel(DevDesc d, const T* __
   Store<T>::store16(v_out + o, vf);
 }
 
-__global__ __launch_bounds__(256) void reconstruct3_bf16_kernel(DevDesc d, const bf16_t* __restrict__ sk,
-                                                                const bf16_t* __restrict__ sv,
-                                                                const int32_t* __restrict__ tok_pos,
-                                                                const int32_t* __restrict__ count, int cap,
-                                                                bf16_t* __restrict__ k_out,
-                                                                bf16_t* __restrict__ v_out) {
+// bf16 storage, three or four rows: the rows are flipped and reduced on their packed
+// bits (v_med3_f16 / packed min and max order bf16 bit patterns like the values
+// they encode; the mean of the two middle values of four is taken in float32 and
+// rounded once).
+template <int R>
+__global__ __launch_bounds__(256) void reconstruct_bf16_kernel(DevDesc d, const bf16_t* __restrict__ sk,
+                                                               const bf16_t* __restrict__ sv,
+                                                               const int32_t* __restrict__ tok_pos,
+                                                               const int32_t* __restrict__ count, int cap,
+                                                               bf16_t* __restrict__ k_out,
+                                                               bf16_t* __restrict__ v_out) {
   constexpr int LPT = 16, TPB = 256 / LPT;
   const int unit = blockIdx.y;
   const int n = clampi(count[unit], 0, cap);
@@ -42,21 +47,23 @@ __global__ __launch_bounds__(256) void reconstruct3_bf16_kernel(DevDesc d, const
   if (t >= n) return;
   const int c0 = (threadIdx.x % LPT) * 8;
   const int J = tok_pos[(size_t)unit * cap + t];
-  const size_t sk_unit = (size_t)unit * 3 * d.w * D;
-  int h[3];
-  uint32_t fk[3], fv[3];
+  const size_t sk_unit = (size_t)unit * R * d.w * D;
+  uint4 rk[R], rv[R];
 #pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    h[i] = bucket_of(d, i, J);
-    const uint32_t neg = sign_neg(d, i, J) ? 0x80008000u : 0u;
-    fk[i] = (d.sign_mask & 1) ? neg : 0u;
-    fv[i] = (d.sign_mask & 2) ? neg : 0u;
+  for (int i = 0; i < R; ++i) {
+    const size_t o = sk_unit + ((size_t)i * d.w + bucket_of(d, i, J)) * D + c0;
+    rk[i] = *reinterpret_cast<const uint4*>(sk + o);
+    rv[i] = *reinterpret_cast<const uint4*>(sv + o);
   }
-  const uint4 kq = query_piece3(d, sk + sk_unit, h, fk, c0);
-  const uint4 vq = query_piece3(d, sv + sk_unit, h, fv, c0);
+#pragma unroll
+  for (int i = 0; i < R; ++i) {
+    const uint32_t neg = sign_neg(d, i, J) ? 0x80008000u : 0u;
+    rk[i] = xor4(rk[i], (d.sign_mask & 1) ? neg : 0u);
+    rv[i] = xor4(rv[i], (d.sign_mask & 2) ? neg : 0u);
+  }
   const size_t o = ((size_t)unit * cap + t) * D + c0;
-  *reinterpret_cast<uint4*>(k_out + o) = kq;
-  *reinterpret_cast<uint4*>(v_out + o) = vq;
+  *reinterpret_cast<uint4*>(k_out + o) = median_piece<R>(rk, d.median_mode);
+  *reinterpret_cast<uint4*>(v_out + o) = median_piece<R>(rv, d.median_mode);
 }
 
 template <typename T>
@@ -81,9 +88,14 @@ hipError_t launch_reconstruct(const DevDesc& d, int dtype, const void* sk, const
                               const int32_t* tok_pos, const int32_t* count, int cap, void* k_out,
                               void* v_out, hipStream_t st) {
   if (cap <= 0) return hipSuccess;
-  if (dtype == KVR_BF16 && d.r == 3) {
-    hipLaunchKernelGGL(reconstruct3_bf16_kernel, dim3((cap + 15) / 16, d.B * d.Hkv), dim3(256), 0, st, d,
-                       (const bf16_t*)sk, (const bf16_t*)sv, tok_pos, count, cap, (bf16_t*)k_out, (bf16_t*)v_out);
+  if (dtype == KVR_BF16 && (d.r == 3 || d.r == 4)) {
+    const dim3 grid((cap + 15) / 16, d.B * d.Hkv);
+    if (d.r == 3)
+      hipLaunchKernelGGL(reconstruct_bf16_kernel<3>, grid, dim3(256), 0, st, d, (const bf16_t*)sk, (const bf16_t*)sv,
+                         tok_pos, count, cap, (bf16_t*)k_out, (bf16_t*)v_out);
+    else
+      hipLaunchKernelGGL(reconstruct_bf16_kernel<4>, grid, dim3(256), 0, st, d, (const bf16_t*)sk, (const bf16_t*)sv,
+                         tok_pos, count, cap, (bf16_t*)k_out, (bf16_t*)v_out);
     return hipGetLastError();
   }
   if (dtype == KVR_F32) return launch_t<float>(d, sk, sv, tok_pos, count, cap, k_out, v_out, st);

@@ -29,10 +29,36 @@ __device__ __forceinline__ uint32_t pack_bf16_exact(float lo, float hi) {
   return (__float_as_uint(hi) & 0xffff0000u) | (__float_as_uint(lo) >> 16);
 }
 
+// Packed minimum / maximum of two bf16 pairs on their raw bits (same argument as
+// for v_med3_f16: the order of finite values is the same in both formats).
+__device__ __forceinline__ uint32_t pk_min_bits(uint32_t a, uint32_t b) {
+  uint32_t dst;
+  asm("v_pk_min_f16 %0, %1, %2" : "=v"(dst) : "v"(a), "v"(b));
+  return dst;
+}
+__device__ __forceinline__ uint32_t pk_max_bits(uint32_t a, uint32_t b) {
+  uint32_t dst;
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(dst) : "v"(a), "v"(b));
+  return dst;
+}
+// two float32 -> packed bf16, round to nearest even (one instruction on gfx950)
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  uint32_t dst;
+  asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(dst) : "v"(lo), "v"(hi));
+  return dst;
+}
+
 template <int R>
 __device__ __forceinline__ uint32_t median_dword(const uint32_t (&x)[R], int mode) {
   if constexpr (R == 3) {
     return med3_bf16x2(x[0], x[1], x[2]);
+  } else if constexpr (R == 4) {
+    // the two middle values of four: max of the pair minima, min of the pair maxima
+    const uint32_t m1 = pk_max_bits(pk_min_bits(x[0], x[1]), pk_min_bits(x[2], x[3]));
+    const uint32_t m2 = pk_min_bits(pk_max_bits(x[0], x[1]), pk_max_bits(x[2], x[3]));
+    if (mode == KVR_MEDIAN_LOWER) return pk_min_bits(m1, m2);
+    // their mean in float32, rounded once to bf16
+    return cvt_pk_bf16(0.5f * (bf_lo(m1) + bf_lo(m2)), 0.5f * (bf_hi(m1) + bf_hi(m2)));
   } else {
     float lo[R], hi[R];
 #pragma unroll
