@@ -31,7 +31,9 @@
 
 namespace kvr {
 
-template <int G, int R, int CH>
+// MODE: the median rule for an even row count, fixed at compile time so that the
+// inner loops carry no branch on it (it plays no part when R is odd).
+template <int G, int R, int CH, int MODE>
 __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc d, AttendArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int NC = CH / 8;                 // 16-byte pieces per LDS row
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
             uint4 row[R];
 #pragma unroll
             for (int i = 0; i < R; ++i) row[i] = *reinterpret_cast<const uint4*>(s_sk + rb[i] + co);
-            const uint4 m = median_piece<R>(row, d.median_mode);
+            const uint4 m = median_piece<R>(row, MODE);
 #pragma unroll
             for (int g = 0; g < G; ++g) {
               float x = s[k][g];
@@ -266,10 +268,11 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
 #pragma unroll
         for (int j8 = 0; j8 < LPT; ++j8) {
           const int owner = j8 * TPW + tl;
-          const uint2 inf = s_info[(k * ST_WAVES + wave) * 64 + owner];
+          // one lane per token: the lane is its own owner
+          const uint2 inf = (LPT == 1) ? info[k] : s_info[(k * ST_WAVES + wave) * 64 + owner];
           float pg[G];
 #pragma unroll
-          for (int g = 0; g < G; ++g) pg[g] = __shfl(s[k][g], owner);
+          for (int g = 0; g < G; ++g) pg[g] = (LPT == 1) ? s[k][g] : __shfl(s[k][g], owner);
           int rb[R];
           row_offsets<R>(inf, rb, ROWB_LOG2);
           uint32_t fm[R];
@@ -303,7 +306,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
               row[i] = *reinterpret_cast<const uint4*>(s_sk + rb[i] + co);
               if (!(R == 3 && i == 0)) row[i] = xor4(row[i], fm[i]);
             }
-            const uint4 m = median_piece<R>(row, d.median_mode);
+            const uint4 m = median_piece<R>(row, MODE);
             if constexpr (V_MFMA) {
               med[h][j8] = m;
             } else {
@@ -389,10 +392,10 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
 }
 
 
-template <int G, int R, int CH>
+template <int G, int R, int CH, int MODE>
 static hipError_t launch_one(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
   static bool attr_set = false;
-  auto kern = attend_vague_staged_kernel<G, R, CH>;
+  auto kern = attend_vague_staged_kernel<G, R, CH, MODE>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -405,21 +408,23 @@ static hipError_t launch_one(const DevDesc& d, const AttendArgs& a, const Attend
   return hipGetLastError();
 }
 
-template <int G, int R>
+template <int G, int R, int MODE>
 static hipError_t launch_ch(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
   switch (plan.ch) {
-    case 64: return launch_one<G, R, 64>(d, a, plan, st);
-    case 32: return launch_one<G, R, 32>(d, a, plan, st);
-    case 16: return launch_one<G, R, 16>(d, a, plan, st);
-    case 8: return launch_one<G, R, 8>(d, a, plan, st);
+    case 64: return launch_one<G, R, 64, MODE>(d, a, plan, st);
+    case 32: return launch_one<G, R, 32, MODE>(d, a, plan, st);
+    case 16: return launch_one<G, R, 16, MODE>(d, a, plan, st);
+    case 8: return launch_one<G, R, 8, MODE>(d, a, plan, st);
     default: return hipErrorInvalidValue;
   }
 }
 
 template <int G>
 static hipError_t launch_r(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
-  if (d.r == 3) return launch_ch<G, 3>(d, a, plan, st);
-  if (d.r == 4) return launch_ch<G, 4>(d, a, plan, st);
+  if (d.r == 3) return launch_ch<G, 3, KVR_MEDIAN_MIDMEAN>(d, a, plan, st);
+  if (d.r == 4)
+    return d.median_mode == KVR_MEDIAN_LOWER ? launch_ch<G, 4, KVR_MEDIAN_LOWER>(d, a, plan, st)
+                                             : launch_ch<G, 4, KVR_MEDIAN_MIDMEAN>(d, a, plan, st);
   return hipErrorInvalidValue;
 }
 
