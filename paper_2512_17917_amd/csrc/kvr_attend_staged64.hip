@@ -30,9 +30,28 @@ __device__ unsigned long long g_phase_t[2048 * 8 * 16];
     if ((threadIdx.x & 63) == 0 && blockIdx.x < 2048)                             \
       g_phase_t[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (i)] = clock64();    \
   } while (0)
+// wall clock (100 MHz, the same on every CU) and the hardware ids of the wave's CU
+#define KVR_WSTAMP(i)                                                                   \
+  do {                                                                                  \
+    if ((threadIdx.x & 63) == 0 && blockIdx.x < 2048)                                   \
+      g_phase_t[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (i)] = wall_clock64();     \
+  } while (0)
+#define KVR_IDSTAMP(i)                                                                  \
+  do {                                                                                  \
+    if ((threadIdx.x & 63) == 0 && blockIdx.x < 2048)                                   \
+      g_phase_t[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (i)] =                     \
+          (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |               \
+          ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);       \
+  } while (0)
 #else
 #define KVR_STAMP(i) \
   do {               \
+  } while (0)
+#define KVR_WSTAMP(i) \
+  do {                \
+  } while (0)
+#define KVR_IDSTAMP(i) \
+  do {                 \
   } while (0)
 #endif
 
@@ -317,7 +336,7 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
   const int sk_bytes = (R * w * ROWB + 1023) & ~1023;
   unsigned char* s_sk = smem;                                             // one 64-channel chunk
   float* s_part = reinterpret_cast<float*>(smem + sk_bytes);              // [NROW][G][CH]
-  float* s_stat = s_part + NROW * G * CH;                                 // [2][NROW][G]
+  float* s_stat = s_part + NROW * G * CH;                                 // [2][NROW][G] floats of room
   uint4* s_q = reinterpret_cast<uint4*>(s_stat + 2 * NROW * G);           // [G][16]
 
   const int nv = clampi(a.n_vague[unit], 0, a.vague_cap);
@@ -335,6 +354,8 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
   const int n_pieces = R * w * NC;
 
   KVR_STAMP(0);
+  KVR_WSTAMP(12);
+  KVR_IDSTAMP(14);
   __builtin_amdgcn_s_setprio(1);
   // ---- loads first: Vague positions of this wave's tokens, q, and a touch of
   //      this workgroup's share of the unit's two sketches (so that the later
@@ -465,27 +486,23 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
       }
     }
   }
-  // maxima and sums: DPP inside each 16-lane row, the NROW rows of the
-  // workgroup meet in LDS, and every wave folds the NROW values again with one
-  // read per head (lane l takes row l mod 32), a row reduction and one exchange
-  // between the two row pairs
+  // Weights are formed against the wave's own maximum, which needs no barrier; the
+  // workgroup's maximum is put together after the barrier that publishes the first
+  // V chunk, and each wave's sums are rescaled by exp(own maximum - workgroup
+  // maximum) when they are merged.  s_stat: [8 waves][G] maxima, [NROW][G] row sums.
   const int prow = wave * 4 + (lane >> 4);
+  float lsum[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    mx[g] = row_max(mx[g]);
-    if ((lane & 15) == 0) s_stat[prow * G + g] = mx[g];
-  }
-  lds_barrier();
-  float lsum[G], M[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float x = row_max(s_stat[(lane & (NROW - 1)) * G + g]);
-    M[g] = fmaxf(x, __shfl_xor(x, 16));
+    float x = row_max(mx[g]);
+    x = fmaxf(x, __shfl_xor(x, 16));
+    x = fmaxf(x, __shfl_xor(x, 32));
+    if (lane == 0) s_stat[wave * G + g] = x;
     lsum[g] = 0.f;
 #pragma unroll
     for (int k = 0; k < KMAX; ++k) {
       if (k >= n_k) break;
-      const float p = (s[k][g] == -__builtin_inff()) ? 0.f : __expf(s[k][g] - M[g]);
+      const float p = (s[k][g] == -__builtin_inff()) ? 0.f : __expf(s[k][g] - x);
       s[k][g] = p;                 // from here on s holds the weights
       lsum[g] += p;
     }
@@ -493,21 +510,9 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     lsum[g] = row_sum<1>(lsum[g]);
-    if ((lane & 15) == 0) s_stat[NROW * G + prow * G + g] = lsum[g];
+    if ((lane & 15) == 0) s_stat[ST_WAVES * G + prow * G + g] = lsum[g];
   }
-  lds_barrier();
   const size_t part = (size_t)unit_l * a.n_slices + a.n_rslices + opaque_s(__builtin_amdgcn_readfirstlane(vs));
-  if (wave == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float x = row_sum<1>(s_stat[NROW * G + (lane & (NROW - 1)) * G + g]);
-      x += __shfl_xor(x, 16);
-      if (lane == 0) {
-        a.part_ml[(part * G + g) * 2] = M[g];
-        a.part_ml[(part * G + g) * 2 + 1] = x;
-      }
-    }
-  }
 
   // ---- weights into matrix-core operand form ----------------------------------
   // Lane `sub` of quad t needs, for the quad's 4 tokens, the weight of head
@@ -556,10 +561,45 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
   // that 8 neighbouring lanes always cover 8 different 16-byte bank groups
   const int pa = sub + ((tl & 1) ? 4 : 0);
   const int pb = sub + ((tl & 1) ? 0 : 4);
+  float* s_fw = s_stat + (ST_WAVES + NROW) * G;     // [8 waves][G]: exp(wave maximum - workgroup maximum)
+  float pend_v = 0.f;                      // chunk 0's output element of this thread, stored one barrier later
   for (int cc = 0; cc < NPH; ++cc) {
     stage_wait();
     lds_barrier();
     KVR_STAMP(7 + 2 * cc);
+    if (cc == 0) {
+      // every wave's maximum and row sums are visible now (this wave's own maximum is
+      // read back too: it would not survive in registers without being spilled)
+      float mo[G], mw[G], mr[G], sr[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        mo[g] = s_stat[(lane & 7) * G + g];                          // maximum of wave (lane mod 8)
+        mw[g] = s_stat[wave * G + g];
+        // lane l < 32 takes row l, which belongs to wave l / 4
+        mr[g] = s_stat[((lane & (NROW - 1)) >> 2) * G + g];
+        sr[g] = s_stat[ST_WAVES * G + (lane & (NROW - 1)) * G + g];
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float M = dpp_max<0x121>(mo[g]);
+        M = dpp_max<0x122>(M);
+        M = dpp_max<0x124>(M);                               // over 8 neighbouring lanes = all 8 waves
+        // kept in LDS rather than in registers through the V phases; only this wave reads it back
+        if (lane == 0) s_fw[wave * G + g] = (mw[g] == -__builtin_inff()) ? 0.f : __expf(mw[g] - M);
+        if (wave == 0) {
+          const float fr = (mr[g] == -__builtin_inff()) ? 0.f : __expf(mr[g] - M);
+          float x = row_sum<1>(sr[g] * fr);
+          x += __shfl_xor(x, 16);
+          if (lane == 0) {
+            a.part_ml[(part * G + g) * 2] = M;
+            a.part_ml[(part * G + g) * 2 + 1] = x;
+          }
+        }
+      }
+    } else if (tid < G * CH) {
+      // chunk cc - 1's element; its latency now hides under this chunk's arithmetic
+      a.part_o[part * G * D + (tid / CH) * D + (cc - 1) * CH + (tid % CH)] = pend_v;
+    }
     // One accumulator set serves both passes.  Pass 0 sums piece pa of the quad's
     // own tokens; then neighbouring quads (lane ^ 4) trade accumulators, so that
     // every lane now holds its neighbour's sums for the piece it takes in pass 1
@@ -585,9 +625,11 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
     if constexpr (true) {
       float o[G][8];
 #pragma unroll
-      for (int g = 0; g < G; ++g)
+      for (int g = 0; g < G; ++g) {
+        const float f = s_fw[wave * G + g];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) o[g][c] = dpp_add<0x128>(acc[c][g]);
+        for (int c = 0; c < 8; ++c) o[g][c] = dpp_add<0x128>(acc[c][g]) * f;
+      }
       if ((lane & 15) < 8) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -598,16 +640,21 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) vo
       }
     }
     lds_barrier();
-    for (int idx = tid; idx < G * CH; idx += ST_THREADS) {
+    static_assert(G * CH <= ST_THREADS, "one output element per thread and chunk");
+    if (tid < G * CH) {
       float v = 0.f;
 #pragma unroll
-      for (int pr = 0; pr < NROW; ++pr) v += s_part[pr * G * CH + idx];
-      a.part_o[part * G * D + (idx / CH) * D + cc * CH + (idx % CH)] = v;
+      for (int pr = 0; pr < NROW; ++pr) v += s_part[pr * G * CH + tid];
+      // The wait before the next barrier would also wait for this store: all but the
+      // last chunk's element are held back until that barrier has passed.
+      if (cc + 1 < NPH) pend_v = v;
+      else a.part_o[part * G * D + (tid / CH) * D + cc * CH + (tid % CH)] = v;
     }
     // the next iteration's barrier (after its stage_wait) orders these reads
     // before the next writes into s_part
   }
   KVR_STAMP(11);
+  KVR_WSTAMP(13);
 }
 
 #ifdef KVR_PHASE_TIMING
