@@ -24,10 +24,15 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 constexpr int STAGED_KMAX = 6;                    // wave-rounds (64 tokens) per wave, staged kernel
 constexpr int STAGED_LDS_LIMIT = 160 * 1024;      // LDS per workgroup on gfx950
 
+// Tokens per slice: about 1280 slices per launch (measured on the 32k workloads: fewer, larger slices leave
+// the merge kernel fewer partials to fold and cost the retained kernel nothing), in multiples of
+// 64 tokens, at least 128 when a unit has a long list (a workgroup of four waves with a single 16-token tile
+// per wave is mostly start-up), at most 1024.
 static int slice_tokens_for(long long tokens, long long units) {
-  long long st = (tokens * units + 2047) / 2048;
+  long long st = (tokens * units + 1279) / 1280;
   st = (st + 63) / 64 * 64;
-  if (st < 64) st = 64;
+  const long long mn = tokens >= 1024 ? 128 : 64;
+  if (st < mn) st = mn;
   if (st > 1024) st = 1024;
   return (int)st;
 }
