@@ -54,7 +54,8 @@ def check_out(out_gpu, out_ref, dtype):
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("r,w,mode,mask", [(3, 37, 0, 2), (1, 5, 0, 2), (2, 9, 0, 2), (2, 9, 1, 3),
                                            (4, 21, 0, 2), (4, 21, 1, 2), (5, 11, 0, 1), (8, 6, 0, 2),
-                                           (6, 7, 1, 0), (3, 1, 0, 2)])
+                                           (6, 7, 1, 0), (3, 1, 0, 2), (4, 13, 0, 3), (4, 13, 1, 1),
+                                           (3, 17, 0, 3), (3, 9, 0, 0)])
 def test_reconstruct_bit_exact(kvr, dtype, r, w, mode, mask):
     say("reconstruct", dtype, r, w, mode, mask)
     rng = np.random.default_rng(100 + r * 7 + w)
