@@ -52,6 +52,12 @@
  *     of bytes kvr_workspace_size reports for that call; its contents need not
  *     survive between calls.  Calls that share one workspace must be ordered on
  *     one stream.
+ *   - Value range.  Inputs are expected to be finite.  With bf16 storage and
+ *     r = 3 or 4 the median over the sketch rows may be taken on the packed bit
+ *     patterns, which is exact for finite values below 2^121 in magnitude;
+ *     sketch contents beyond that (or Inf / NaN) give unspecified medians in
+ *     kvr_reconstruct, kvr_attend_decode and kvr_attend_multi.  Every other
+ *     configuration has no such limit.
  */
 #ifndef KVR_H
 #define KVR_H
