@@ -6,9 +6,12 @@
 // them, which is the point of batching them.
 //
 //   1. the dense kernel below runs over the retained slots,
-//   2. and again over the Vague index list: with three sketch rows it rebuilds each
-//      16-token tile itself (sketch rows gathered from L2, median by selection; a
-//      rebuilt piece serves all columns and never reaches memory); otherwise
+//   2. the Vague index list goes through the LDS-staged kernel of
+//      kvr_attend_multi_staged.hip when the sketch allows it (three rows, values
+//      signed only, a 64-channel chunk fits LDS); else the dense kernel runs again
+//      over the list: with three sketch rows it rebuilds each 16-token tile itself
+//      (sketch rows gathered from L2, median by selection; a rebuilt piece serves
+//      all columns and never reaches memory); otherwise
 //      kvr_reconstruct's kernel first writes the rebuilt tokens to workspace (one
 //      layer's worth) and the dense kernel reads them like retained rows,
 //   3. the merge kernel of kvr_attend_decode combines the slice partials, writes
@@ -279,20 +282,25 @@ MultiPlan attend_multi_plan(const DevDesc& d, int n_q, long long ret_cap, long l
   const int ncol = n_q * d.G;
   p.rslice_tokens = attend_slice_tokens(ret_cap, units);
   p.n_rslices = (int)((ret_cap + p.rslice_tokens - 1) / p.rslice_tokens);
-  p.vslice_tokens = vague_cap > 0 ? attend_slice_tokens(vague_cap, units) : 64;
+  p.staged = vague_cap > 0 && multi_staged_applies(d, vague_cap);
+  if (p.staged) p.vslice_tokens = multi_staged_part_tokens(vague_cap, units);
+  else p.vslice_tokens = vague_cap > 0 ? attend_slice_tokens(vague_cap, units) : 64;
   p.n_vslices = vague_cap > 0 ? (int)((vague_cap + p.vslice_tokens - 1) / p.vslice_tokens) : 0;
   p.n_slices = p.n_rslices + p.n_vslices;
+  // the staged kernel reads its scratch arrays (records in the first rebuilt-token area, partial logits in
+  // the second, final logits) a few tiles past the end without clamping
+  const size_t pad = p.staged ? (size_t)multi_staged_pad_tokens() * ncol * sizeof(float) : 0;
   size_t off = 0;
   p.off_khat = off;
-  off = align_up_m(off + (size_t)units * vague_cap * D * sizeof(uint16_t), 256);
+  off = align_up_m(off + (size_t)units * vague_cap * D * sizeof(uint16_t) + pad, 256);
   p.off_vhat = off;
-  off = align_up_m(off + (size_t)units * vague_cap * D * sizeof(uint16_t), 256);
+  off = align_up_m(off + (size_t)units * vague_cap * D * sizeof(uint16_t) + pad, 256);
   p.off_part_o = off;
   off = align_up_m(off + (size_t)units * p.n_slices * ncol * D * sizeof(float), 256);
   p.off_part_ml = off;
   off = align_up_m(off + (size_t)units * p.n_slices * ncol * 2 * sizeof(float), 256);
   p.off_logits = off;
-  off = align_up_m(off + (size_t)units * (size_t)(ret_cap + vague_cap) * ncol * sizeof(float), 256);
+  off = align_up_m(off + (size_t)units * (size_t)(ret_cap + vague_cap) * ncol * sizeof(float) + pad, 256);
   p.total_bytes = off;
   return p;
 }
@@ -308,7 +316,7 @@ static hipError_t launch_multi_n(const DevDesc& d, const AttendArgs& a0, const i
   // rebuilt piece serves all columns of the tile and never reaches memory); otherwise
   // they go through the workspace
   const bool in_kernel = d.r == 3 && d.w <= 65535;
-  if (a0.vague_cap > 0 && !in_kernel) {
+  if (a0.vague_cap > 0 && !in_kernel && !plan.staged) {
     e = launch_reconstruct(d, KVR_BF16, a0.sk, a0.sv, a0.vague_pos, a0.n_vague, a0.vague_cap, khat, vhat, st);
     if (e != hipSuccess) return e;
   }
@@ -335,7 +343,14 @@ static hipError_t launch_multi_n(const DevDesc& d, const AttendArgs& a0, const i
   e = launch_dense<NCOL>(d, da, st);
   if (e != hipSuccess) return e;
   // rebuilt Vague tokens
-  if (a0.vague_cap > 0) {
+  if (a0.vague_cap > 0 && plan.staged) {
+    // the rebuilt-token areas of the workspace are free on this route: they hold the token records and
+    // the logits after the first K chunk (8 + 4 NCOL <= 256 bytes per token)
+    e = launch_attend_multi_staged(d, a0, n_ctx, n_q, plan.vslice_tokens, plan.n_vslices, plan.n_rslices,
+                                   plan.n_slices, da.part_o, da.part_ml, (float*)(base + plan.off_logits), khat,
+                                   vhat, st);
+    if (e != hipSuccess) return e;
+  } else if (a0.vague_cap > 0) {
     da.k = khat;
     da.v = vhat;
     if (in_kernel) {

@@ -74,7 +74,7 @@ hipError_t launch_reconstruct(const DevDesc& d, int dtype, const void* sk, const
 hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, const AttendPlan& plan,
                          hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
 
-// tokens per slice when `tokens` tokens of each of `units` units are cut for about 2048 workgroups
+// tokens per slice when `tokens` tokens of each of `units` units are cut for about 1280 workgroups
 int attend_slice_tokens(long long tokens, long long units);
 
 // merge kernel alone: n_cols = partial columns per unit (G for one query, n_q * G for several)
@@ -83,8 +83,17 @@ hipError_t launch_attend_combine(const DevDesc& d, const AttendArgs& a, int n_co
 // kvr_attend_multi: workspace carve-up and launch (bf16, n_q * G in {1, 2, 4, 8, 16})
 struct MultiPlan {
   int rslice_tokens, n_rslices, vslice_tokens, n_vslices, n_slices;
+  bool staged;           // Vague list through the LDS-staged kernel (vslice_tokens / n_vslices = its parts)
   size_t off_khat, off_vhat, off_part_o, off_part_ml, off_logits, total_bytes;
 };
+// LDS-staged kernel of kvr_attend_multi over the Vague list (bf16, r = 3, values signed only, 3 w <= 1024)
+bool multi_staged_applies(const DevDesc& d, long long vague_cap);
+int multi_staged_part_tokens(long long vague_cap, long long units);
+int multi_staged_pad_tokens();   // tokens the staged kernel may read past the end of its scratch arrays
+hipError_t launch_attend_multi_staged(const DevDesc& d, const AttendArgs& a, const int32_t* n_ctx, int n_q,
+                                      int part_tokens, int n_parts, int slice0, int n_slices, float* part_o,
+                                      float* part_ml, float* logits, void* scratch_rec, void* scratch_partial,
+                                      hipStream_t st);
 MultiPlan attend_multi_plan(const DevDesc& d, int n_q, long long ret_cap, long long vague_cap);
 hipError_t launch_attend_multi(const DevDesc& d, const AttendArgs& a, const int32_t* n_ctx, int n_q,
                                const MultiPlan& plan, void* ws, hipStream_t st);

@@ -75,6 +75,16 @@ def test_attend_multi_follows_the_oracle(kvr, LayerState, n_q, heads):
     run_multi_case(kvr, LayerState, wl, 0, n_q)
 
 
+def test_attend_multi_short_vague_list(kvr, LayerState):
+    """Fewer than 64 Vague tokens: the list is not worth staging the sketch through LDS for; the dense kernel
+    rebuilds its tiles from sketch rows gathered out of memory."""
+    say("attend multi, short Vague list")
+    wl = S.small_workload("mqshort", batch=1, n_q_heads=8, n_kv_heads=2, context=300, budget=0.9, r=3, steps=5,
+                          cfg_id=87)
+    assert wl.n_vague0 + 3 < 64
+    run_multi_case(kvr, LayerState, wl, 0, 4)
+
+
 def test_attend_multi_even_rows_and_no_scores(kvr, LayerState):
     say("attend multi r=4, scores off")
     wl = S.small_workload("mq4r", batch=1, n_q_heads=8, n_kv_heads=2, context=700, budget=0.3, r=4, steps=5,
