@@ -312,6 +312,7 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
     };
     const int col_c = col_live ? col : 0;
     const unsigned char* s_vcol = s_sk + 8 * col;
+    const float m_safe = (m_run == NEG_INF) ? 0.f : m_run;    // a column without any visible token: all weights 0
     auto v_loads = [&](int ti, VIn& in) {
       // padded scratch arrays: no clamp (what lies past the end of the list is masked later)
       const int tt0 = t_begin + ti * 16 + 4 * r16;
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
         const bool ok = t0 + 4 * r16 + j < t_end;
         rj[j] = ok ? cur.rj[j] : make_uint2(0u, 0u);
         const float sl = (ok && col_live) ? cur.s[j] : NEG_INF;
-        p[j] = (sl == NEG_INF) ? 0.f : __expf(sl - m_run);
+        p[j] = __expf(sl - m_safe);                       // -inf (masked, or past the end) gives 0
         if (cc == 0) l_run += p[j];
         // the sign two of the token's three rows agree on goes onto the weight
         p[j] = __uint_as_float(__float_as_uint(p[j]) ^ (rj[j].x << 31));
