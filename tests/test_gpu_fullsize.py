@@ -204,6 +204,48 @@ def test_c4_layer_in_bench_configuration():
     assert bool((ls.sketch_k == sk_before)[untouched].all())
     say("full size: swaps per unit: min", int(n_sw.min()), "max", int(n_sw.max()), "mean", float(n_sw.float().mean()))
 
+    # ---- several queries at once (kvr_attend_multi) on this state: the four newest tokens are the
+    #      queries' own positions.  Sampled units against the oracle; every unit against dense causal
+    #      attention over the library's reconstruction.
+    say("full size: attend_multi, 4 queries")
+    NQ = 4
+    qm = S.queries_many(wl, layer, 10, NQ, device=dev).transpose(0, 1).contiguous()        # [B, NQ, Hq, D]
+    scores_before = ls.scores.clone()
+    outm = ls.attend_multi(qm, NQ).clone()
+    torch.cuda.synchronize()
+    q_pos = np.arange(n_ctx - NQ, n_ctx)
+    for (b, h), st in zip(SAMPLED, states):
+        qq = U.to_np(qm[b, :, h * G:(h + 1) * G])
+        o_ref, sc_ref, _ = O.attend_multi(qq, q_pos, st.K_ret, st.V_ret, st.ret_pos, st.SK, st.SV, params,
+                                          st.vague_pos, st.n_ctx, scale, scores=st.scores, storage="bf16")
+        assert np.abs(outm[b, :, h * G:(h + 1) * G].cpu().double().numpy() - o_ref).max() <= 2e-2
+        assert np.abs(ls.scores[b, h].cpu().double().numpy() - sc_ref.astype(np.float64)).max() <= 2e-5 * NQ
+    nv = int(ls.n_vague.max())
+    kh = torch.zeros(B, Hkv, nv, D, dtype=ls.dtype, device=dev)
+    vh = torch.zeros_like(kh)
+    kvr.kvr_reconstruct(d, ls.sketch_k, ls.sketch_v, ls.vague_pos[:, :, :nv].contiguous(), ls.n_vague, nv, kh, vh)
+    live = torch.arange(nv, device=dev).view(1, 1, nv) < ls.n_vague.unsqueeze(-1)
+    pos_all = torch.cat([ls.ret_pos, torch.where(live, ls.vague_pos[:, :, :nv], torch.full_like(ls.vague_pos[:, :, :nv], -1))],
+                        dim=2).long()                                                          # [B, Hkv, n]
+    Kall = torch.cat([ls.k_ret, kh], dim=2).double()
+    Vall = torch.cat([ls.v_ret, vh], dim=2).double()
+    inc = torch.zeros(B, Hkv, pos_all.shape[2], dtype=torch.float64, device=dev)
+    worst = 0.0
+    for t in range(NQ):
+        qf = qm[:, t].double().view(B, Hkv, G, D)
+        logit = torch.einsum("bhgd,bhnd->bhgn", qf, Kall) * scale
+        seen = (pos_all >= 0) & (pos_all <= n_ctx - NQ + t)
+        logit = logit.masked_fill(~seen.unsqueeze(2), float("-inf"))
+        pr = torch.softmax(logit, dim=-1)
+        ref = torch.einsum("bhgn,bhnd->bhgd", pr, Vall).reshape(B, Hq, D)
+        worst = max(worst, ((outm[:, t].double() - ref).abs().max() / ref.abs().max()).item())
+        inc += pr.sum(dim=2)
+    say("full size: attend_multi max relative |out - dense over reconstruction| =", worst)
+    assert worst <= 3e-5
+    got_inc = (ls.scores.double() - scores_before.double()).gather(2, pos_all.clamp(min=0))
+    got_inc = torch.where(pos_all >= 0, got_inc, torch.zeros_like(got_inc))
+    assert (got_inc - inc).abs().max().item() <= 2e-5 * NQ
+
 
 @pytest.mark.parametrize("name,sampled", [("c3", [(0, 5)]), ("c5", [(1, 2), (3, 7)])])
 def test_other_workloads_one_layer_sampled(name, sampled):
