@@ -162,6 +162,11 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
   for (int cc = 0; cc < 2; ++cc) {
     if (cc > 0) lds_barrier();                                // every wave is done with the previous chunk
     stage_issue_swz<true>(skg, s_sk, n_pieces, cc, tid);
+    if (cc == 0) {
+      // under the first chunk copy: the record of every token of this workgroup, one token per thread
+      // (hashed once, not once per lane group that needs it); published by the barrier below
+      for (int t = t_begin + tid; t < t_end; t += MS_THREADS) recs[t] = make_record3(d, w, pp[t]);
+    }
     // q of this lane's column, channels 64 cc + 32 kx + 8 r16 .. + 7
     uint4 qb[2];
     {
@@ -181,8 +186,7 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
     // wait for any read with a write outstanding drains everything: arranged like this, every such wait
     // only covers requests that are a whole tile old.
     struct KIn {
-      int J;              // first chunk: position of token t0 + col
-      uint2 rec;          // second chunk: its record
+      uint2 rec;          // record of token t0 + col
       float prev[4];      // second chunk: partial logits of tokens t0 + 4 r16 + i, this lane's column
       int tpos[4];        //               and their positions
     };
@@ -190,16 +194,12 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
     const int col_c = col_live ? col : 0;
     auto k_loads = [&](int ti, KIn& in) {
       const int t0 = t_begin + ti * 16;
-      const int tk = min(t0 + col, t_last);
-      in.J = -1;
       in.rec = make_uint2(0u, 0u);
 #pragma unroll
       for (int i = 0; i < 4; ++i) { in.prev[i] = 0.f; in.tpos[i] = -1; }
-      if (cc == 0) {
-        in.J = pp[tk];
-      } else {
-        // the scratch arrays are padded: reads past the end of the list need no clamp (masked later)
-        in.rec = recs[t0 + col];
+      // the scratch arrays are padded: reads past the end of the list need no clamp (masked later)
+      in.rec = recs[t0 + col];
+      if (cc == 1) {
         const float* pv = partial + (size_t)(t0 + 4 * r16) * NCOL + col_c;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -210,11 +210,9 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
     };
     // results of the previous tile, not yet stored
     int st_t0 = -1;
-    uint2 st_rec = make_uint2(0u, 0u);
     float st_v[4] = {0.f, 0.f, 0.f, 0.f};
     auto k_stores = [&]() {
       if (st_t0 < 0) return;
-      if (cc == 0 && r16 == 0 && st_t0 + col < t_end) recs[st_t0 + col] = st_rec;
       if (col_live) {
         float* dst = (cc == 0) ? partial : logits;
 #pragma unroll
@@ -230,7 +228,7 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
       const int t0 = t_begin + (wave + MS_WAVES * k) * 16;
       // the tile's inputs must have arrived here (empty statement that reads them), before the
       // previous tile's stores and the next tile's loads are issued
-      if (cc == 0) asm volatile("" ::"v"(cur.J));
+      if (cc == 0) asm volatile("" ::"v"(cur.rec.x), "v"(cur.rec.y));
       else asm volatile("" ::"v"(cur.rec.x), "v"(cur.rec.y), "v"(cur.prev[0]), "v"(cur.prev[1]), "v"(cur.prev[2]),
                         "v"(cur.prev[3]), "v"(cur.tpos[0]), "v"(cur.tpos[1]), "v"(cur.tpos[2]), "v"(cur.tpos[3]));
       __builtin_amdgcn_sched_barrier(0);
@@ -240,7 +238,6 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
       __builtin_amdgcn_sched_barrier(0);
       const bool tk_ok = t0 + col < t_end;
       uint2 rec = cur.rec;
-      if (cc == 0) rec = make_record3(d, w, cur.J);
       if (!tk_ok) rec = make_uint2(0u, 0u);
       int rb[3];
       record_rows(rec, rb);
@@ -265,7 +262,6 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
         S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8ms_t, ka[kx]),
                                                     __builtin_bit_cast(bf16x8ms_t, qb[kx]), S, 0, 0, 0);
       st_t0 = t0;
-      st_rec = rec;
       if (cc == 0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) st_v[i] = S[i];
