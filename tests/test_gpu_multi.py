@@ -85,6 +85,70 @@ def test_attend_multi_short_vague_list(kvr, LayerState):
     run_multi_case(kvr, LayerState, wl, 0, 4)
 
 
+def test_attend_multi_ragged_device_counts(kvr):
+    """The Vague list of every unit has its own length on the device: empty, one token, around a tile
+    boundary, around a workgroup's share, full, negative and oversized (clamped).  Reference: float64 dense
+    causal attention over kvr_reconstruct's output (which test_gpu_parity ties to the oracle bit for bit)."""
+    say("attend multi, ragged device counts")
+    rng = np.random.default_rng(77)
+    B, Hq, Hkv, r, w, D, n_q = 5, 4, 2, 3, 40, 128, 4
+    G = Hq // Hkv
+    ret_cap, vague_cap = 70, 900
+    counts = np.array([[0, 1], [15, 16], [17, 255], [257, 900], [-3, 5000]], dtype=np.int32)
+    dt = torch.bfloat16
+    d = kvr.make_desc(B, Hq, Hkv, r, w, dt, seed=31)
+    dev = "cuda"
+    n_ctx_val = ret_cap + vague_cap
+    q = torch.randn(B, n_q, Hq, D, device=dev).to(dt)
+    k_ret = torch.randn(B, Hkv, ret_cap, D, device=dev).to(dt)
+    v_ret = torch.randn(B, Hkv, ret_cap, D, device=dev).to(dt)
+    sk = (3 * torch.randn(B, Hkv, r, w, D, device=dev)).to(dt)
+    sv = (3 * torch.randn(B, Hkv, r, w, D, device=dev)).to(dt)
+    ret_pos = torch.empty(B, Hkv, ret_cap, dtype=torch.int32, device=dev)
+    vague_pos = torch.empty(B, Hkv, vague_cap, dtype=torch.int32, device=dev)
+    for b in range(B):
+        for h in range(Hkv):
+            perm = torch.as_tensor(rng.permutation(n_ctx_val).astype(np.int32))
+            ret_pos[b, h] = perm[:ret_cap].to(dev)
+            vague_pos[b, h] = perm[ret_cap:].to(dev)
+    ret_pos[1, 0, 5:9] = -1                                              # a few empty slots
+    n_vague = torch.as_tensor(counts).to(dev)
+    n_ctx = torch.full((B,), n_ctx_val, dtype=torch.int32, device=dev)
+    scores = torch.rand(B, Hkv, n_ctx_val, device=dev)
+    scores0 = scores.clone()
+    out = torch.full((B, n_q, Hq, D), 9.0, dtype=torch.float32, device=dev)
+    ws = torch.empty(kvr.kvr_attend_multi_workspace_size(d, n_q, ret_cap, vague_cap), dtype=torch.uint8, device=dev)
+    kvr.kvr_attend_multi(d, q, n_q, n_ctx, k_ret, v_ret, ret_pos, ret_cap, sk, sv, vague_pos, n_vague, vague_cap,
+                         out, scores, n_ctx_val, ws)
+    kh = torch.zeros(B, Hkv, vague_cap, D, dtype=dt, device=dev)
+    vh = torch.zeros_like(kh)
+    kvr.kvr_reconstruct(d, sk, sv, vague_pos, n_vague, vague_cap, kh, vh)
+    torch.cuda.synchronize()
+    nv = n_vague.clamp(0, vague_cap)
+    live = torch.arange(vague_cap, device=dev).view(1, 1, -1) < nv.unsqueeze(-1)
+    pos_all = torch.cat([ret_pos, torch.where(live, vague_pos, torch.full_like(vague_pos, -1))], dim=2).long()
+    Kall = torch.cat([k_ret, kh], dim=2).double()
+    Vall = torch.cat([v_ret, vh], dim=2).double()
+    inc = torch.zeros(B, Hkv, pos_all.shape[2], dtype=torch.float64, device=dev)
+    for t in range(n_q):
+        qf = q[:, t].double().view(B, Hkv, G, D)
+        logit = torch.einsum("bhgd,bhnd->bhgn", qf, Kall) * d.softmax_scale
+        seen = (pos_all >= 0) & (pos_all <= n_ctx_val - n_q + t)
+        logit = logit.masked_fill(~seen.unsqueeze(2), float("-inf"))
+        pr = torch.softmax(logit, dim=-1)
+        ref = torch.einsum("bhgn,bhnd->bhgd", pr, Vall).reshape(B, Hq, D)
+        err = (out[:, t].double() - ref).abs().max().item()
+        assert err <= 3e-5 * ref.abs().max().item(), (t, err)
+        inc += pr.sum(dim=2)
+    got = (scores.double() - scores0.double()).gather(2, pos_all.clamp(min=0))
+    got = torch.where(pos_all >= 0, got, torch.zeros_like(got))
+    assert (got - inc).abs().max().item() <= 2e-5 * n_q
+    # positions that are in neither set keep their scores
+    touched = torch.zeros(B, Hkv, n_ctx_val + 1, dtype=torch.bool, device=dev)
+    touched.scatter_(2, torch.where(pos_all >= 0, pos_all, torch.full_like(pos_all, n_ctx_val)), True)
+    assert bool(((scores == scores0) | touched[:, :, :n_ctx_val]).all())
+
+
 def test_attend_multi_even_rows_and_no_scores(kvr, LayerState):
     say("attend multi r=4, scores off")
     wl = S.small_workload("mq4r", batch=1, n_q_heads=8, n_kv_heads=2, context=700, budget=0.3, r=4, steps=5,
