@@ -22,8 +22,9 @@
 //     register transpose gives the four B operands; instruction c leaves the lane
 //     with the sums of columns 4 r16 + {0..3} for channel 4 col + c.
 // Softmax: the K-chunk-1 phase knows the final logits, so each wave takes the
-// maximum of its own tiles per column there; weights are formed against that
-// maximum and the waves' sums are rescaled when they meet.
+// maximum of its tiles per column there; the V phases form the weights against
+// the workgroup's maximum (the waves' maxima meet in LDS in between).
+// Tiles are handed to the waves through a counter in LDS, phase by phase.
 //
 // LDS layout: row-major, 128 bytes per sketch slot, but piece p of slot s is kept
 // at piece position p xor (s mod 8): the 16 lanes that read the same piece of 16
@@ -134,6 +135,7 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
   unsigned char* s_sk = smem;                                        // chunk; later [waves][NCOL][64] floats
   float* s_max = reinterpret_cast<float*>(smem + sk_bytes);          // [waves][16]
   float* s_sum = s_max + MS_WAVES * 16;                              // [waves][16]
+  int* s_ctr = reinterpret_cast<int*>(s_sum + MS_WAVES * 16);        // next tile of the running phase
 
   const int b = unit / d.Hkv, hk = unit % d.Hkv;
   const int rows = clampi(a.n_valid[unit], 0, a.cap);
@@ -154,7 +156,14 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
   const bool col_live = col < NCOL;
   const int qpos = a.n_ctx[b] - a.n_q + tq;
 
-  const int n_mine = n_tiles > wave ? (n_tiles - wave + MS_WAVES - 1) / MS_WAVES : 0;   // this wave's tiles
+  // Tiles are handed out through a counter in LDS, phase by phase: of the four waves that share a SIMD the
+  // ones started first win the issue arbitration, and with a fixed share each the workgroup would wait for
+  // its slowest wave at the end of every phase.
+  auto next_tile = [&]() {
+    int t = 0;
+    if (lane == 0) t = atomicAdd(s_ctr, 1);
+    return __builtin_amdgcn_readfirstlane(t);
+  };
 
   KVR_MS_STAMP(0);
   // ---- K phases -----------------------------------------------------------------------------------
@@ -178,6 +187,7 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
         if (!col_live) qb[kx] = make_uint4(0u, 0u, 0u, 0u);
       }
     }
+    if (tid == 0) *s_ctr = 0;
     stage_wait();
     lds_barrier();
     // What a tile needs from memory is requested one tile ahead with unconditional loads (indices clamped
@@ -224,8 +234,8 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
     };
     // Two input buffers take the tiles in turn (copying a buffer would wait for its loads).  A tile past
     // the end of this wave's share computes on clamped inputs and leaves nothing behind.
-    auto k_tile = [&](const KIn& cur, KIn& nxt, int k) {
-      const int t0 = t_begin + (wave + MS_WAVES * k) * 16;
+    auto k_tile = [&](const KIn& cur, KIn& nxt, int ti, int ti_next) {
+      const int t0 = t_begin + ti * 16;
       // the tile's inputs must have arrived here (empty statement that reads them), before the
       // previous tile's stores and the next tile's loads are issued
       if (cc == 0) asm volatile("" ::"v"(cur.rec.x), "v"(cur.rec.y));
@@ -234,7 +244,7 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
       __builtin_amdgcn_sched_barrier(0);
       k_stores();
       __builtin_amdgcn_sched_barrier(0);
-      k_loads(wave + MS_WAVES * (k + 1), nxt);
+      k_loads(ti_next, nxt);
       __builtin_amdgcn_sched_barrier(0);
       const bool tk_ok = t0 + col < t_end;
       uint2 rec = cur.rec;
@@ -276,10 +286,14 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
       }
     };
     KIn in_a, in_b;
-    k_loads(wave, in_a);
-    for (int k = 0; k < n_mine; k += 2) {
-      k_tile(in_a, in_b, k);
-      k_tile(in_b, in_a, k + 1);
+    int ti = next_tile();
+    k_loads(ti, in_a);
+    while (ti < n_tiles) {
+      const int t1 = next_tile();
+      k_tile(in_a, in_b, ti, t1);
+      const int t2 = next_tile();
+      k_tile(in_b, in_a, t1, t2);
+      ti = t2;
     }
     k_stores();
     KVR_MS_STAMP(1 + cc);
@@ -295,6 +309,14 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
   for (int cc = 0; cc < 2; ++cc) {
     lds_barrier();                                            // every wave is done with the previous chunk
     stage_issue_swz<false>(svg, s_sk, n_pieces, cc, tid);
+    if (tid == 0) *s_ctr = 0;
+    if (cc == 0) {
+      // a wave meets other tiles here than in the K phases: weights against the workgroup's maximum
+      float M = s_max[col];
+#pragma unroll
+      for (int w_ = 1; w_ < MS_WAVES; ++w_) M = fmaxf(M, s_max[w_ * 16 + col]);
+      m_run = M;
+    }
     stage_wait();                                             // also: this wave's logits stores have landed
     lds_barrier();
     f32x4_t acc[4];                                           // acc[c][i]: column 4 r16 + i, channel 64 cc + 4 col + c
@@ -320,9 +342,9 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
         in.s[j] = lp[j * NCOL];
       }
     };
-    auto v_tile = [&](const VIn& cur, VIn& nxt, int k) {
-      const int t0 = t_begin + (wave + MS_WAVES * k) * 16;
-      v_loads(wave + MS_WAVES * (k + 1), nxt);
+    auto v_tile = [&](const VIn& cur, VIn& nxt, int ti, int ti_next) {
+      const int t0 = t_begin + ti * 16;
+      v_loads(ti_next, nxt);
       uint2 rj[4];
       float p[4];
 #pragma unroll
@@ -368,10 +390,14 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
       for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bop[c], acc[c], 0, 0, 0);
     };
     VIn in_a, in_b;
-    v_loads(wave, in_a);
-    for (int k = 0; k < n_mine; k += 2) {
-      v_tile(in_a, in_b, k);
-      v_tile(in_b, in_a, k + 1);
+    int ti = next_tile();
+    v_loads(ti, in_a);
+    while (ti < n_tiles) {
+      const int t1 = next_tile();
+      v_tile(in_a, in_b, ti, t1);
+      const int t2 = next_tile();
+      v_tile(in_b, in_a, t1, t2);
+      ti = t2;
     }
     KVR_MS_STAMP(3 + 2 * cc);
     if (cc == 0) {
@@ -399,10 +425,8 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
       float L = 0.f, O = 0.f;
 #pragma unroll
       for (int w_ = 0; w_ < MS_WAVES; ++w_) {
-        const float mw = s_max[w_ * 16 + c_];
-        const float e = (mw == NEG_INF) ? 0.f : __expf(mw - M);
-        L += s_sum[w_ * 16 + c_] * e;
-        O += s_acc[((size_t)w_ * NCOL + c_) * CH + ch] * e;
+        L += s_sum[w_ * 16 + c_];
+        O += s_acc[((size_t)w_ * NCOL + c_) * CH + ch];
       }
       a.part_o[(part * NCOL + c_) * D + cc * CH + ch] = O;
       if (cc == 0 && ch == 0) {
@@ -443,7 +467,7 @@ static hipError_t launch_n(const DevDesc& d, const MultiStagedArgs& a, hipStream
   size_t chunk = ((size_t)3 * d.w * 128 + 1023) & ~(size_t)1023;
   const size_t merge = (size_t)MS_WAVES * NCOL * 64 * 4;
   if (chunk < merge) chunk = merge;
-  const size_t lds = chunk + 2 * MS_WAVES * 16 * sizeof(float);
+  const size_t lds = chunk + 2 * MS_WAVES * 16 * sizeof(float) + 16;
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   const int units = d.B * d.Hkv;
   const int units_pad = (units + 7) / 8 * 8;
