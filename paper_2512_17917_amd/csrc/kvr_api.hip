@@ -268,6 +268,9 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret
   a.part_o = (float*)(base + plan.off_part_o);
   a.part_ml = (float*)(base + plan.off_part_ml);
   a.logits = scores ? (float*)(base + plan.off_logits) : nullptr;
+  a.logits_buf = (float*)(base + plan.off_logits);
+  a.scratch_rec = plan.streamed ? (void*)(base + plan.off_rec) : nullptr;
+  a.scratch_partial = plan.streamed ? (void*)(base + plan.off_partial) : nullptr;
   a.n_q = 1;
   const hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;
   g_ev_start = g_ev_stop = nullptr;

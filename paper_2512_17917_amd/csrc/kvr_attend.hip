@@ -83,12 +83,18 @@ AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long
     }
   }
   p.mfma_retained = (dtype == KVR_BF16);
+  // 8 query heads per kv head: too many logits per token for the register-resident staged kernels; the
+  // streaming kernel of kvr_attend_multi takes the list with the 8 heads as its columns (one query)
+  p.streamed = !p.staged && dtype == KVR_BF16 && d.G == 8 && multi_staged_applies(d, vague_cap);
   p.vslice_tokens = 0;
   if (p.mfma_retained || p.staged) {
     // retained slots and the Vague list are cut separately
     p.rslice_tokens = slice_tokens_for(ret_cap, units);
     p.n_rslices = (int)((ret_cap + p.rslice_tokens - 1) / p.rslice_tokens);
-    if (!p.staged && vague_cap > 0) {
+    if (p.streamed) {
+      p.vslice_tokens = multi_staged_part_tokens(vague_cap, units);
+      p.n_vslices = (int)((vague_cap + p.vslice_tokens - 1) / p.vslice_tokens);
+    } else if (!p.staged && vague_cap > 0) {
       p.vslice_tokens = slice_tokens_for(vague_cap, units);
       p.n_vslices = (int)((vague_cap + p.vslice_tokens - 1) / p.vslice_tokens);
     }
@@ -105,8 +111,16 @@ AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long
   off = align_up(off + (size_t)units * p.n_slices * d.G * D * sizeof(float), 256);
   p.off_part_ml = off;
   off = align_up(off + (size_t)units * p.n_slices * d.G * 2 * sizeof(float), 256);
+  // the streaming kernel reads its arrays a few tiles past the end without clamping
+  const size_t pad_tok = p.streamed ? (size_t)multi_staged_pad_tokens() : 0;
   p.off_logits = off;
-  off = align_up(off + (size_t)units * (size_t)tot_cap * d.G * sizeof(float), 256);
+  off = align_up(off + ((size_t)units * (size_t)tot_cap + pad_tok) * d.G * sizeof(float), 256);
+  p.off_rec = p.off_partial = off;
+  if (p.streamed) {
+    off = align_up(off + ((size_t)units * (size_t)vague_cap + pad_tok) * 8, 256);
+    p.off_partial = off;
+    off = align_up(off + ((size_t)units * (size_t)vague_cap + pad_tok) * d.G * sizeof(float), 256);
+  }
   p.total_bytes = off;
   return p;
 }
@@ -539,6 +553,11 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
     // already launched above
   } else if (e == hipSuccess && plan.staged) {
     e = launch_attend_vague_staged(d, a, plan, st);
+  } else if (e == hipSuccess && plan.streamed && plan.n_vslices > 0) {
+    // no causal mask in a decode call: every listed token is visible (n_ctx = null)
+    e = launch_attend_multi_staged(d, a, nullptr, 1, plan.vslice_tokens, plan.n_vslices, plan.n_rslices,
+                                   plan.n_slices, a.part_o, a.part_ml, a.logits_buf, a.scratch_rec,
+                                   a.scratch_partial, st);
   } else if (e == hipSuccess && plan.mfma_retained && plan.n_vslices > 0) {
     a.slice_tokens = plan.vslice_tokens;
     a.tok_start = a.ret_cap;

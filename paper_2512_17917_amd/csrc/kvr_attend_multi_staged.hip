@@ -43,7 +43,7 @@ constexpr int MS_PAD_TOKENS = 4 * MS_WAVES * 16;
 
 struct MultiStagedArgs {
   const bf16_t* q;          // [B, n_q, Hq, D]
-  const int32_t* n_ctx;     // [B]
+  const int32_t* n_ctx;     // [B], or null: every listed token is visible to every query
   int n_q;
   const bf16_t* sk;         // [units, 3, w, D]
   const bf16_t* sv;
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
   // this lane's column: query tq, head g
   const int tq = col / d.G, g = col % d.G;
   const bool col_live = col < NCOL;
-  const int qpos = a.n_ctx[b] - a.n_q + tq;
+  const int qpos = a.n_ctx ? a.n_ctx[b] - a.n_q + tq : 0x7fffffff;   // no n_ctx: no causal mask (decode call)
 
   // Tiles are handed out through a counter in LDS, phase by phase: of the four waves that share a SIMD the
   // ones started first win the issue arbitration, and with a fixed share each the workgroup would wait for

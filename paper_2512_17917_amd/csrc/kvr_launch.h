@@ -20,7 +20,9 @@ struct AttendPlan {
   int vslice_tokens;    // generic kernel over the Vague list: tokens per slice
   int ch;               // staged: channels per LDS phase
   int lds_bytes;        // staged: dynamic LDS per workgroup
-  size_t off_part_o, off_part_ml, off_logits, total_bytes;
+  bool streamed;        // Vague tokens by the streaming LDS-staged kernel of kvr_attend_multi with one query
+                        // (8 query heads per kv head; vslice_tokens / n_vslices are its parts)
+  size_t off_part_o, off_part_ml, off_logits, off_rec, off_partial, total_bytes;
 };
 AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long vague_cap);
 
@@ -42,6 +44,9 @@ struct AttendArgs {
   float* part_o;     // [units, n_slices, G, D]
   float* part_ml;    // [units, n_slices, G, 2]
   float* logits;     // [units, ret_cap + vague_cap, G] or nullptr when scores == nullptr
+  float* logits_buf; // the same area, always (the streaming kernel needs the logits itself)
+  void* scratch_rec; // streaming kernel: token records / partial logits (null when the plan is not streamed)
+  void* scratch_partial;
   int n_slices;      // partial results per unit (all kinds)
   int slice_tokens;  // generic / retained kernel: tokens per slice
   int tok_start;     // generic kernel: first token it handles

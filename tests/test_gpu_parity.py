@@ -409,6 +409,20 @@ def test_attend_staged_channel_chunks(kvr):
     run_attend_case(kvr, rng, dtype, 3, 12, 3, 3, 50, 70, [4000, 3999, 1, 0, 64, 65, 2500, 4100, 128], 4100)
 
 
+def test_attend_eight_heads_per_kv_head(kvr):
+    """bf16, r = 3, G = 8: the Vague list goes through the streaming LDS-staged kernel (the one of
+    kvr_attend_multi, one query, 8 columns): several workgroups per unit, ragged tiles, empty and clamped
+    lists, with and without score accumulation."""
+    rng = np.random.default_rng(58)
+    dtype = torch.bfloat16
+    for (w, nv, cap, ret, sc) in [(40, [900, 64, 0, 257], 900, 70, True),
+                                  (273, [1500, 1499], 1500, 130, True),
+                                  (7, [300, -2, 5000, 17], 400, 20, False)]:
+        say("attend G=8 streamed", w, nv)
+        B = len(nv)
+        run_attend_case(kvr, rng, dtype, B, 8, 1, 3, w, ret, nv, cap, with_scores=sc)
+
+
 def test_attend_staged64_shapes(kvr):
     """bf16, r = 3, 64-channel chunks: the specialised staged kernel.  Group sizes 1, 2, 4; widths from a few
     slots to the widest sketch that still fits LDS; 1 to 6 rounds of 64 tokens per wave; lists that end inside
