@@ -312,8 +312,10 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q,
 /*
  * The Calculation Phase for n_q query tokens per sequence at once (a chunk of
  * prompt or of drafted tokens): as the Overview describes the phase, the layer's
- * cache is rebuilt once (Algorithm 4; Vague tokens by Algorithm 2, written to
- * workspace and read back once) and attention then runs over it for all queries.
+ * cache is rebuilt once (Algorithm 4; Vague tokens by Algorithm 2: inside the
+ * attention kernel, one rebuilt piece serving all queries, for bf16 sketches of
+ * three rows; otherwise written to workspace and read back once) and attention
+ * then runs over it for all queries.
  * Query t of sequence b sits at position n_ctx[b] - n_q + t (the n_q newest
  * tokens, already pushed into the Recent part) and attends over the tokens at
  * positions <= its own:
@@ -327,8 +329,9 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q,
  *   q          dev [B, n_q, Hq, D] bf16, read;   n_ctx dev int32 [B], read
  *   k_ret .. vague_cap, scores, n_cap   as for kvr_attend_decode (ret_pos must not be NULL)
  *   out        dev float32 [B, n_q, Hq, D], written
- *   ws         per kvr_attend_multi_workspace_size(desc, n_q, ret_cap, vague_cap): the rebuilt
- *              Vague tokens of all units (2 * vague_cap * D * 2 bytes per unit), slice partials, logits
+ *   ws         per kvr_attend_multi_workspace_size(desc, n_q, ret_cap, vague_cap): room for the rebuilt
+ *              Vague tokens of all units (2 * vague_cap * D * 2 bytes per unit; per-token scratch of the
+ *              in-kernel routes lives there too), slice partials, logits
  */
 int32_t kvr_attend_multi_workspace_size(const kvr_desc* desc, int32_t n_q, int64_t ret_cap, int64_t vague_cap,
                                         size_t* bytes);
