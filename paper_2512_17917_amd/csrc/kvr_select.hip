@@ -97,10 +97,30 @@ __global__ __launch_bounds__(SEL_THREADS) void step_update_kernel(
       pre[j] = (s < ret_cap) ? rp[s] : 0;
     }
   }
-  (void)append_body_pre<T, SEL_THREADS, SEL_KPT>(d, unit, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap, pre);
+  // the new token's rows are requested with the positions, one round trip ahead of their store
+  uint4 row_in = make_uint4(0u, 0u, 0u, 0u);
+  {
+    constexpr int LPT = D / Store<T>::VEC;
+    const int t = threadIdx.x;
+    if (t < LPT) row_in = *reinterpret_cast<const uint4*>(k_new + (size_t)unit * D + t * Store<T>::VEC);
+    else if (t < 2 * LPT) row_in = *reinterpret_cast<const uint4*>(v_new + (size_t)unit * D + (t - LPT) * Store<T>::VEC);
+  }
+  // the scores the selection will rank by are requested now: their round trip overlaps the append
+  float pre_sc[SEL_KPT];
+  {
+    const float* sc = scores + (size_t)unit * n_cap;
+    const int recent_from = n_ctx[unit / d.Hkv] - n_recent;
+#pragma unroll
+    for (int j = 0; j < SEL_KPT; ++j) {
+      const int pos = pre[j];
+      pre_sc[j] = (pos >= 0 && pos < recent_from && pos < n_cap) ? sc[pos] : 0.f;
+    }
+  }
+  (void)append_body_pre<T, SEL_THREADS, SEL_KPT>(d, unit, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap, pre,
+                                                 &row_in);
   __syncthreads();          // the new row and its ret_pos entry are visible to the whole workgroup
   select_body<true>(d, unit, scores, n_cap, ret_pos, ret_cap, n_ctx, n_recent, k_cand, evict_slot, evict_pos,
-                    n_evict, evict_cap, vague_pos, n_vague, vague_cap, pre);
+                    n_evict, evict_cap, vague_pos, n_vague, vague_cap, pre, pre_sc);
   __syncthreads();          // the eviction list and its count are visible
   encode_small_body<T>(d, unit, k_ret, v_ret, ret_cap, evict_slot, evict_pos, n_evict, evict_cap, sk, sv,
                        nullptr, nullptr);

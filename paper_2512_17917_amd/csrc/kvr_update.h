@@ -82,7 +82,10 @@ template <typename T, int NT, int KPT>
 __device__ __forceinline__ int append_body_pre(const DevDesc& d, int unit, const T* __restrict__ k_new,
                                                const T* __restrict__ v_new, const int32_t* __restrict__ n_ctx,
                                                T* __restrict__ k_ret, T* __restrict__ v_ret,
-                                               int32_t* __restrict__ ret_pos, int ret_cap, const int (&pre)[KPT]) {
+                                               int32_t* __restrict__ ret_pos, int ret_cap, const int (&pre)[KPT],
+                                               const uint4* row_in = nullptr) {
+  // row_in (may be null): this thread's 16 bytes of the new K row (tid < LPT) or V row (tid < 2 LPT),
+  // loaded by the caller ahead of time
   constexpr int VEC = Store<T>::VEC;
   constexpr int LPT = D / VEC;
   const int tid = threadIdx.x;
@@ -102,11 +105,11 @@ __device__ __forceinline__ int append_body_pre(const DevDesc& d, int unit, const
   if (s >= ret_cap) return -1;
   const size_t dst = ((size_t)unit * ret_cap + s) * D;
   if (tid < LPT) {
-    const uint4 v = *reinterpret_cast<const uint4*>(k_new + (size_t)unit * D + tid * VEC);
+    const uint4 v = row_in ? *row_in : *reinterpret_cast<const uint4*>(k_new + (size_t)unit * D + tid * VEC);
     *reinterpret_cast<uint4*>(k_ret + dst + tid * VEC) = v;
   } else if (tid < 2 * LPT) {
     const int l2 = tid - LPT;
-    const uint4 v = *reinterpret_cast<const uint4*>(v_new + (size_t)unit * D + l2 * VEC);
+    const uint4 v = row_in ? *row_in : *reinterpret_cast<const uint4*>(v_new + (size_t)unit * D + l2 * VEC);
     *reinterpret_cast<uint4*>(v_ret + dst + l2 * VEC) = v;
   }
   if (tid == 0) rp[s] = n_ctx[unit / d.Hkv] - 1;
@@ -122,6 +125,18 @@ __device__ __forceinline__ bool pos_key(int pos, const float* __restrict__ sc, i
   if (slot >= ret_cap) return false;
   if (pos < 0 || pos >= recent_from || pos >= n_cap) return false;
   uint32_t b = __float_as_uint(sc[pos]);
+  if (b == 0x80000000u) b = 0u;                                   // -0 ranks as +0
+  const uint32_t mono = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
+  key = ((unsigned long long)mono << 32) | (uint32_t)(~(uint32_t)pos);
+  return true;
+}
+
+// the same with the token's score already in a register (scv = scores[pos], read only if pos is eligible)
+__device__ __forceinline__ bool pos_key_val(int pos, float scv, int slot, int ret_cap, int recent_from,
+                                            long long n_cap, unsigned long long& key) {
+  if (slot >= ret_cap) return false;
+  if (pos < 0 || pos >= recent_from || pos >= n_cap) return false;
+  uint32_t b = __float_as_uint(scv);
   if (b == 0x80000000u) b = 0u;                                   // -0 ranks as +0
   const uint32_t mono = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
   key = ((unsigned long long)mono << 32) | (uint32_t)(~(uint32_t)pos);
@@ -202,13 +217,15 @@ __device__ __forceinline__ void pick_digit(SelShared& sh, int byte) {
 // pre (REG only, may be null): positions of this thread's slots as they were
 // before a token was appended in this same launch; the appended token is Recent
 // and therefore ranks like an empty slot, so the stale value serves.
+// pre_sc (with pre, may be null): the scores at those positions, gathered by the
+// caller ahead of time (valid where the position is eligible).
 template <bool REG, int KPT = SEL_KPT>
 __device__ __forceinline__ void select_body(
     const DevDesc& d, int unit, const float* __restrict__ scores, long long n_cap,
     int32_t* __restrict__ ret_pos, int ret_cap, const int32_t* __restrict__ n_ctx, int n_recent, int k_cand,
     int32_t* __restrict__ evict_slot, int32_t* __restrict__ evict_pos, int32_t* __restrict__ n_evict,
     int evict_cap, int32_t* __restrict__ vague_pos, int32_t* __restrict__ n_vague, int vague_cap,
-    const int* pre = nullptr) {
+    const int* pre = nullptr, const float* pre_sc = nullptr) {
   const int b = unit / d.Hkv;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -238,8 +255,9 @@ __device__ __forceinline__ void select_body(
 #pragma unroll
       for (int j = 0; j < KPT; ++j) {
         unsigned long long key = KEY_NONE;
-        const bool ok = pre ? pos_key(pre[j], sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key)
-                            : slot_key(rp, sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key);
+        const bool ok = pre_sc ? pos_key_val(pre[j], pre_sc[j], j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key)
+                        : pre  ? pos_key(pre[j], sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key)
+                               : slot_key(rp, sc, j * SEL_THREADS + tid, ret_cap, recent_from, n_cap, key);
         rkey[j] = ok ? key : KEY_NONE;
         c += ok ? 1 : 0;
       }
