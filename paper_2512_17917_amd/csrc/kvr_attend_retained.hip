@@ -140,7 +140,7 @@ __device__ __forceinline__ void compute_tile(const RetTile& t, const uint4 (&qb)
 }
 
 template <int G>
-__global__ __launch_bounds__(256) void attend_retained_kernel(DevDesc d, AttendArgs a, int n_rslices) {
+__device__ __forceinline__ void attend_retained_body(const DevDesc& d, const AttendArgs& a, int n_rslices) {
   constexpr int NW = 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r16 = lane >> 4, col = lane & 15;
@@ -226,12 +226,35 @@ __global__ __launch_bounds__(256) void attend_retained_kernel(DevDesc d, AttendA
   }
 }
 
+// Two kernels around the same body.  Alone, the kernel takes the registers it likes (135 for G = 4).  Next to
+// the staged kernel it is capped at 124 + 4 accumulation registers (the attribute counts in units of two on
+// this target): 2 x 192 (two waves of the staged kernel, which then needs no spills) + 128 fill a SIMD's 512
+// registers exactly; the few spills of this kernel, which waits for HBM most of the time, cost nothing.
+template <int G>
+__global__ __launch_bounds__(256) void attend_retained_kernel(DevDesc d, AttendArgs a, int n_rslices) {
+  attend_retained_body<G>(d, a, n_rslices);
+}
+template <int G>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(62))) void attend_retained_shared_kernel(
+    DevDesc d, AttendArgs a, int n_rslices) {
+  attend_retained_body<G>(d, a, n_rslices);
+}
+
 hipError_t launch_attend_retained(const DevDesc& d, const AttendArgs& a, int n_rslices, int max_wgs,
                                   hipStream_t st) {
   int n_wgs = d.B * d.Hkv * n_rslices;
   if (max_wgs > 0 && n_wgs > max_wgs) n_wgs = max_wgs;
   if (n_wgs < 1) return hipSuccess;
   const dim3 grid(n_wgs), block(256);
+  if (max_wgs > 0) {                    // launched next to the staged kernel
+    switch (d.G) {
+      case 1: hipLaunchKernelGGL(attend_retained_shared_kernel<1>, grid, block, 0, st, d, a, n_rslices); break;
+      case 2: hipLaunchKernelGGL(attend_retained_shared_kernel<2>, grid, block, 0, st, d, a, n_rslices); break;
+      case 4: hipLaunchKernelGGL(attend_retained_shared_kernel<4>, grid, block, 0, st, d, a, n_rslices); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   switch (d.G) {
     case 1: hipLaunchKernelGGL(attend_retained_kernel<1>, grid, block, 0, st, d, a, n_rslices); break;
     case 2: hipLaunchKernelGGL(attend_retained_kernel<2>, grid, block, 0, st, d, a, n_rslices); break;

@@ -312,10 +312,11 @@ __device__ __forceinline__ void v_pass(const unsigned char* s_sk, const uint2 (&
 static_assert(ST_KMAX == 6, "KVR_DISPATCH_NK covers 1..6 rounds");
 
 template <int G>
-// Register cap: 184 per lane (the attribute counts in units of two on this target).  Two
-// waves of this kernel and one wave of the retained-slot kernel then fit a SIMD's 512
-// registers together, which is what lets the two kernels run side by side on a CU.
-__global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(92))) void attend_vague_staged64_kernel(
+// Register cap: 192 per lane (the attribute counts in units of two on this target).  Two
+// waves of this kernel and one wave of the retained-slot kernel in its 128-register form
+// then fill a SIMD's 512 registers exactly, which is what lets the two kernels run side by
+// side on a CU.
+__global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(96))) void attend_vague_staged64_kernel(
     DevDesc d, AttendArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int R = 3, CH = 64, NC = 8, ROWB = 128, ROWB_LOG2 = 7, NPH = D / CH, KMAX = ST_KMAX;
