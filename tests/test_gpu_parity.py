@@ -409,6 +409,18 @@ def test_attend_staged_channel_chunks(kvr):
     run_attend_case(kvr, rng, dtype, 3, 12, 3, 3, 50, 70, [4000, 3999, 1, 0, 64, 65, 2500, 4100, 128], 4100)
 
 
+@pytest.mark.parametrize("G", [1, 2])
+def test_attend_side_by_side_small_groups(kvr, G):
+    """Enough units and Vague tokens that the staged kernel fills the chip more than twice over: the
+    retained-slot kernel then runs next to it, in its register-capped form, also for 1 and 2 query heads
+    per kv head (the full-size test covers 4)."""
+    rng = np.random.default_rng(59 + G)
+    B, Hkv = 16, 8
+    nv = [9300 - 7 * (i % 5) for i in range(B * Hkv)]
+    say("attend side by side", G)
+    run_attend_case(kvr, rng, torch.bfloat16, B, Hkv * G, Hkv, 3, 60, 150, nv, 9400)
+
+
 def test_attend_eight_heads_per_kv_head(kvr):
     """bf16, r = 3, G = 8: the Vague list goes through the streaming LDS-staged kernel (the one of
     kvr_attend_multi, one query, 8 columns): several workgroups per unit, ragged tiles, empty and clamped
