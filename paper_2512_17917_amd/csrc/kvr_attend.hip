@@ -535,12 +535,14 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
   if (side != nullptr) {
     e = hipEventRecord(side->fork, st);
     if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
-    if (e == hipSuccess) e = launch_attend_retained(d, a, plan.n_rslices, cu_count(), side->stream);
+    const bool s64 = d.r == 3 && plan.ch == 64 && 3 * d.w <= 1024;          // the 64-channel staged kernel runs
+    const int reg_form = s64 ? 1 : ((d.G == 4 && plan.ch <= 16) ? 2 : 0);
+    if (e == hipSuccess) e = launch_attend_retained(d, a, plan.n_rslices, cu_count(), reg_form, side->stream);
     if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
     if (e == hipSuccess) e = launch_attend_vague_staged(d, a, plan, st);
     if (e == hipSuccess) e = hipStreamWaitEvent(st, side->join, 0);
   } else if (plan.mfma_retained) {
-    e = launch_attend_retained(d, a, plan.n_rslices, 0, st);
+    e = launch_attend_retained(d, a, plan.n_rslices, 0, 0, st);
   } else {
     a.tok_limit = plan.staged ? a.ret_cap : a.ret_cap + a.vague_cap;
     dim3 grid(plan.n_rslices, units);

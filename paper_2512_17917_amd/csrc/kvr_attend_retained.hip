@@ -240,13 +240,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(62))) void atte
   attend_retained_body<G>(d, a, n_rslices);
 }
 
+// Third form, 76 + 4 registers: what two waves of the general staged kernel with 16- or 8-channel chunks and
+// four query heads (about 212 registers each) leave of a SIMD.  It spills a lot and is slow, but it has six
+// times the general staged kernel's duration to finish in.
+template <int G>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(38))) void attend_retained_tight_kernel(
+    DevDesc d, AttendArgs a, int n_rslices) {
+  attend_retained_body<G>(d, a, n_rslices);
+}
+
 hipError_t launch_attend_retained(const DevDesc& d, const AttendArgs& a, int n_rslices, int max_wgs,
-                                  hipStream_t st) {
+                                  int reg_form, hipStream_t st) {
   int n_wgs = d.B * d.Hkv * n_rslices;
   if (max_wgs > 0 && n_wgs > max_wgs) n_wgs = max_wgs;
   if (n_wgs < 1) return hipSuccess;
   const dim3 grid(n_wgs), block(256);
-  if (max_wgs > 0) {                    // launched next to the staged kernel
+  if (reg_form == 2 && d.G == 4) {      // next to the general staged kernel in its widest form
+    hipLaunchKernelGGL(attend_retained_tight_kernel<4>, grid, block, 0, st, d, a, n_rslices);
+    return hipGetLastError();
+  }
+  if (reg_form == 1) {                  // next to the 64-channel staged kernel
     switch (d.G) {
       case 1: hipLaunchKernelGGL(attend_retained_shared_kernel<1>, grid, block, 0, st, d, a, n_rslices); break;
       case 2: hipLaunchKernelGGL(attend_retained_shared_kernel<2>, grid, block, 0, st, d, a, n_rslices); break;

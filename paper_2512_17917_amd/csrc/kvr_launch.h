@@ -60,8 +60,10 @@ struct AttendArgs {
 
 // Retained slots by the MFMA kernel (bf16): slices 0 .. n_rslices-1 of a.slice_tokens slots.
 // max_wgs > 0 caps the launch width (the workgroups then walk the items with a grid stride).
+// reg_form: 0 = the kernel takes the registers it likes; 1 = capped at 128 (it shares the SIMDs with the
+// 64-channel staged kernel); 2 = capped at 80 (with the general staged kernel's widest form; G = 4 only).
 hipError_t launch_attend_retained(const DevDesc& d, const AttendArgs& a, int n_rslices, int max_wgs,
-                                  hipStream_t st);
+                                  int reg_form, hipStream_t st);
 
 struct EncodePlan {
   bool bulk;
