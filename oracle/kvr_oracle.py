@@ -362,6 +362,7 @@ class UnitState:
         self.SK, self.SV = sketch_zeros(r, w, D)
         self.vague_pos = []
         self.n_ctx = 0
+        self.r_size = 0              # R.size: the Recent queue holds the r_size newest positions
         self.params = params
         self.storage = storage
         self.n_recent = n_recent
@@ -383,13 +384,23 @@ class UnitState:
         self.V_ret[slot] = v
         self.ret_pos[slot] = self.n_ctx
         self.n_ctx += 1
+        self.r_size += 1             # R.Push(T)
         return slot
 
-    def compress(self):
-        """Algorithm 3 with Slack = 0 and without the swap loop: whatever exceeds
-        the Recent and Candidate budgets goes into the sketch."""
+    def compress(self, slack=0):
+        """Algorithm 3 without the swap loop, after R.Push.  The Recent part is a
+        queue over the r_size newest positions; n_recent is R.budget.
+            if R.size > R.budget + Slack:  C.Push(R.Pop_k(R.size - R.budget))
+        i.e. only when the queue has outgrown its budget by more than `slack` do its
+        oldest R.size - R.budget tokens leave it, all at once; then
+            while C.size > C.budget:  V.Insert(C.Top_Pop())
+        moves the lowest-score Candidates into the sketch (one insert call in
+        ascending slot order: a slot shared by several of them is rounded once).
+        slack = 0: one token in, one token out per step."""
+        if self.r_size > self.n_recent + slack:
+            self.r_size = self.n_recent
         ev_slots, ev_pos = select(self.scores, self.ret_pos, self.n_ctx,
-                                  self.n_recent, self.k_candidate)
+                                  self.r_size, self.k_candidate)
         if len(ev_slots):
             self.SK, self.SV = insert(self.SK, self.SV, self.params, ev_pos,
                                       self.K_ret[ev_slots], self.V_ret[ev_slots],
@@ -406,7 +417,7 @@ class UnitState:
         done = []
         for _ in range(max_swaps):
             pick = swap_pick(self.scores, self.ret_pos, self.vague_pos, self.n_ctx,
-                             self.n_recent, replace_rate)
+                             self.r_size, replace_rate)
             if pick is None:
                 break
             s_min, i_max = pick
@@ -424,11 +435,11 @@ class UnitState:
             median_mode=self.median_mode, sign_mask=self.sign_mask)
         return out, p
 
-    def decode_step(self, k_new, v_new, q, scale, *, replace_rate=None, max_swaps=0):
+    def decode_step(self, k_new, v_new, q, scale, *, replace_rate=None, max_swaps=0, slack=0):
         """append -> select -> insert -> (swap loop, if replace_rate is given) ->
         rebuild + attend + accumulate scores."""
         self.append(k_new, v_new)
-        ev = self.compress()
+        ev = self.compress(slack)
         if replace_rate is not None and max_swaps > 0:
             self.swap_back(replace_rate, max_swaps)
         out, p = self.attend(q, scale)
@@ -447,6 +458,7 @@ def dense_prefill_state(K, V, q0, scale, r, w, params, storage, *, n_recent, k_c
     st.V_ret[:N] = V
     st.ret_pos[:N] = np.arange(N)
     st.n_ctx = N
+    st.r_size = N                    # every prompt token was pushed into the Recent queue
     _, p = attention(q0, st.K_ret[:N], st.V_ret[:N], scale)
     st.scores[:N] = p.sum(axis=0).astype(np.float32)
     return st

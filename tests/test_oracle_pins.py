@@ -720,6 +720,131 @@ def test_swap_loop_exit_condition_and_partition():
     assert len(st2.swap_back(1.1, 0)) == 0
 
 
+# ------------------------------------------------------------------ Slack (Algorithm 3, first branch)
+def _slack_run(slack, steps, seed=41, N=44, n_recent=5, k_cand=7, w=3):
+    """A prompt and `steps` decode steps with the given Slack; yields the state and
+    what each step evicted."""
+    rng = np.random.default_rng(seed)
+    D, r = 128, 3
+    params = O.hash_params_from_seed(9, r)
+    K = O.to_storage(rng.standard_normal((N + steps, D)), "bf16")
+    V = O.to_storage(rng.standard_normal((N + steps, D)), "bf16")
+    q = O.to_storage(rng.standard_normal((steps + 1, 2, D)), "bf16")
+    scale = 1 / math.sqrt(D)
+    st = O.dense_prefill_state(K[:N], V[:N], q[0], scale, r, w, params, "bf16", n_recent=n_recent,
+                               k_candidate=k_cand, n_cap=N + steps + 2, acc_dtype=np.float32)
+    st.compress(slack)
+    st = O.compact(st, n_recent + k_cand + slack + 1)
+    hist = []
+    for t in range(steps):
+        scores_before = st.scores.copy()
+        ret_before = st.ret_pos.copy()
+        out, (es, ep), _ = st.decode_step(K[N + t], V[N + t], q[t + 1], scale, slack=slack)
+        hist.append((es.copy(), ep.copy(), scores_before, ret_before, st.r_size, st.n_ctx,
+                     st.ret_pos.copy(), list(st.vague_pos), out))
+    return st, hist, (K, V, q, params, scale)
+
+
+def test_slack_zero_is_one_in_one_out_with_a_fixed_recent_window():
+    """Slack = 0: the Recent part is always the n_recent newest positions and every step
+    evicts exactly the lowest-score candidate (explicit sort, not the oracle's select)."""
+    st, hist, _ = _slack_run(0, 9)
+    n_recent, k_cand = 5, 7
+    for (es, ep, sc, rp, r_size, n_ctx, rp_after, vague, _) in hist:
+        assert r_size == n_recent and len(es) == 1
+        cand = [int(p) for p in rp if 0 <= p < n_ctx - n_recent]        # rp: before the append (the new token is Recent)
+        assert len(cand) == k_cand + 1
+        lowest = sorted(cand, key=lambda p: (float(sc[p]), -p))[0]
+        assert int(ep[0]) == lowest
+        assert sorted(int(p) for p in rp_after if p >= 0)[-n_recent:] == list(range(n_ctx - n_recent, n_ctx))
+
+
+@pytest.mark.parametrize("slack", [1, 3, 7])
+def test_slack_batches_evictions(slack):
+    """Slack = s: the Recent queue grows from its budget to budget + s, then s + 1 tokens
+    leave it at once and s + 1 tokens (the lowest scores among old Candidates and the
+    popped ones) go into the sketch in one insert."""
+    n_recent, k_cand, steps = 5, 7, 3 * (slack + 1) + 1
+    st, hist, _ = _slack_run(slack, steps)
+    for t, (es, ep, sc, rp, r_size, n_ctx, rp_after, vague, _) in enumerate(hist):
+        phase = (t + 1) % (slack + 1)
+        assert n_recent <= r_size <= n_recent + slack
+        if phase == 0:
+            assert r_size == n_recent and len(es) == slack + 1
+            # Candidates before the pop plus the popped tokens; the slack + 1 lowest leave
+            pool = [int(p) for p in rp if 0 <= p < n_ctx - n_recent]
+            assert len(pool) == k_cand + slack + 1
+            leave = sorted(pool, key=lambda p: (float(sc[p]), -p))[:slack + 1]
+            assert sorted(int(p) for p in ep) == sorted(leave)
+            assert list(es) == sorted(es)                               # listed in ascending slot order
+        else:
+            assert r_size == n_recent + phase and len(es) == 0
+        kept = sorted(int(p) for p in rp_after if p >= 0)
+        assert sorted(kept + vague) == list(range(n_ctx))               # a partition of the context
+        assert kept[-r_size:] == list(range(n_ctx - r_size, n_ctx))    # the queue = the newest r_size positions
+        assert len(kept) == k_cand + r_size
+
+
+@pytest.mark.parametrize("slack", [0, 2, 5])
+def test_slack_against_a_queue_and_a_heap(slack):
+    """Algorithm 3 written out with the paper's own containers -- R a FIFO queue of
+    positions, C a min-heap keyed by cumulative score -- driven by the same score
+    history; after every step the three parts must be the oracle's."""
+    import collections
+    import heapq
+    n_recent, k_cand, steps = 5, 7, 14
+    st, hist, _ = _slack_run(slack, steps, seed=43)
+    N = hist[0][5] - 1
+    # the prompt: every token pushed into R, then the first branch and the pop loop once
+    sc0 = hist[0][2]
+    R = collections.deque(range(N))
+    C, Vg = [], set()
+
+    def settle(scores):
+        if len(R) > n_recent + slack:
+            for _ in range(len(R) - n_recent):
+                C.append(R.popleft())                                   # oldest first
+        heap = [(float(scores[p]), -p, p) for p in C]
+        heapq.heapify(heap)                                             # min score on top; ties: the later position
+        while len(heap) > k_cand:
+            _, _, p = heapq.heappop(heap)
+            Vg.add(p)
+        C[:] = [p for _, _, p in heap]
+
+    settle(sc0)
+    for (es, ep, sc, rp, r_size, n_ctx, rp_after, vague, _) in hist:
+        R.append(n_ctx - 1)
+        before = set(Vg)
+        settle(sc)
+        assert sorted(Vg - before) == sorted(int(p) for p in ep)
+        assert sorted(Vg) == sorted(vague)
+        assert sorted(list(R) + C) == sorted(int(p) for p in rp_after if p >= 0)
+        assert len(R) == r_size
+
+
+def test_slack_shared_slot_is_rounded_once():
+    """Several tokens of one bulk pop land in one sketch slot (3 slots per row, 4 tokens):
+    the sketch after the step equals one insert call of the popped tokens in ascending
+    slot order on the sketch before it, and differs from inserting them one call at a
+    time (which would round the shared slot after every token)."""
+    slack = 3
+    st, hist, (K, V, q, params, scale) = _slack_run(slack, 3)       # state just before the first bulk pop
+    SK0, SV0 = st.SK.copy(), st.SV.copy()
+    N3 = st.n_ctx
+    rng = np.random.default_rng(77)
+    kn = O.to_storage(rng.standard_normal(128) * 37.0, "bf16")
+    vn = O.to_storage(rng.standard_normal(128) * 37.0, "bf16")
+    K_before, V_before = st.K_ret.copy(), st.V_ret.copy()
+    out, (es, ep), _ = st.decode_step(kn, vn, q[1], scale, slack=slack)
+    assert len(es) == 4
+    one_call = O.insert(SK0, SV0, params, ep, K_before[es], V_before[es], storage="bf16", acc_dtype=np.float32)
+    assert np.array_equal(st.SK, one_call[0]) and np.array_equal(st.SV, one_call[1])
+    sk, sv = SK0, SV0
+    for s, p in zip(es, ep):
+        sk, sv = O.insert(sk, sv, params, [p], K_before[[s]], V_before[[s]], storage="bf16", acc_dtype=np.float32)
+    assert not (np.array_equal(sk, st.SK) and np.array_equal(sv, st.SV))
+
+
 # ------------------------------------------------------------------ input recipe: per-layer budgets
 def test_layer_budgets_preserve_the_total():
     import kvr_synth as S
