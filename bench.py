@@ -30,10 +30,24 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the attention pair from the profiler's FETCH_SIZE / WRITE_SIZE counters (scaled by
-# what the same counters read for a kernel of known size); measured off-line, see
-# profiles/attend_pair_c4_hbm_traffic.txt.  Only for the workload it was measured on.
-MEASURED_TRAFFIC_BYTES = {"c4": 310159 * 1024}
+# Off-line counter readings (rocprofv3 --pmc, one run per counter group; the files give the commands), per
+# workload: they cannot be collected inside this program.  `traffic`: HBM bytes per kvr_attend_decode call
+# from FETCH_SIZE / WRITE_SIZE, each scaled by what the same counter reads for a copy kernel of known size
+# and the same access width (None: not measured for this workload).  `alu`: the staged kernel that rebuilds
+# the Vague tokens, which is bound by vector-ALU issue and LDS, not by HBM.
+OFFLINE_COUNTERS = {
+    "c4": {
+        "traffic": None,
+        "traffic_note": "not reported: the FETCH_SIZE reading on hand is below the bytes the retained rows alone "
+                        "account for, so it is not a usable measurement (profiles/attend_pair_c4_hbm_traffic.txt)",
+        "alu": {"file": "profiles/attend_kernels_c4_sq_counters.txt", "kernel": "attend_vague_staged64_kernel<4>",
+                "valu_insts_per_launch": 60055680.0, "waves_per_launch": 10240,
+                "valu_busy": 0.72, "lds_busy": 0.42, "lds_bank_conflict_share": 0.46},
+    },
+}
+# plain vector ALU peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second (the 157.3 TFLOP/s
+# fp32 vector figure / 2 flops per FMA / 2 for packed math, which this build switches off)
+ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
 def algorithmic_bytes_per_unit(wl, n_ctx):
@@ -48,71 +62,71 @@ def algorithmic_bytes_per_unit(wl, n_ctx):
     return 2 * R * D * e + 2 * S * D * e + 4 * a + 8 * n_ctx + 2 * G * D * e
 
 
-class HipEvents:
-    """Raw HIP events (the library records them around its main kernel)."""
-
-    def __init__(self):
-        self.hip = C.CDLL("libamdhip64.so")
-        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
-        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
-        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
-
-    def create(self):
-        ev = C.c_void_p()
-        rc = self.hip.hipEventCreate(C.byref(ev))
-        if rc != 0:
-            raise RuntimeError(f"hipEventCreate failed: {rc}")
-        return ev
-
-    def elapsed_ms(self, a, b):
-        ms = C.c_float()
-        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
-        if rc != 0:
-            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
-        return ms.value
-
-
-def cpu_baseline(wl, n_units, budget_s=20.0):
-    """Time the oracle's decode step on host cores for a few units of the same
-    workload (full shape), scale to the whole job."""
+def _oracle_unit_step(args):
+    """One unit of the workload at full shape: prompt state (not timed), then one
+    decode step of the oracle (timed).  Runs in a worker process."""
+    name, layer, b, h = args
+    os.environ["OMP_NUM_THREADS"] = "1"
     import numpy as np
+    import torch
+    torch.set_num_threads(1)
     import kvr_synth as S
     from oracle import kvr_oracle as O
-
+    try:
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(1)
+    except Exception:
+        pass
+    wl = S.WORKLOADS[name]
     scale = 1.0 / math.sqrt(wl.head_dim)
     G = wl.group
-    layer = 0
     params = O.hash_params_from_seed(S.BASE_SEED + layer, wl.r)
     q0, q1 = S.queries(wl, layer, 0), S.queries(wl, layer, 1)
     kn, vn = S.new_tokens(wl, layer, 0)
     f64 = lambda t: t.to("cpu").double().numpy()
-    times, used = [], []
-    t_start = time.perf_counter()
-    for u in range(n_units):
-        b, h = divmod(u, wl.n_kv_heads)
-        if b >= wl.batch:
-            break
-        K, V = S.kv_unit(wl, layer, b, h)
-        st = O.dense_prefill_state(f64(K), f64(V), f64(q0[b, h * G:(h + 1) * G]), scale, wl.r, wl.w, params,
-                                   wl.dtype, n_recent=wl.n_recent, k_candidate=wl.n_candidate,
-                                   n_cap=wl.context + 2, acc_dtype=np.float32)
-        st.compress()
-        st = O.compact(st, wl.n_retained + 1)
-        t0 = time.perf_counter()
-        st.decode_step(f64(kn[b, h]), f64(vn[b, h]), f64(q1[b, h * G:(h + 1) * G]), scale)
-        times.append(time.perf_counter() - t0)
-        used.append((b, h))
-        if time.perf_counter() - t_start > budget_s:
-            break
-    per_unit = sum(times) / len(times)
+    K, V = S.kv_unit(wl, layer, b, h)
+    st = O.dense_prefill_state(f64(K), f64(V), f64(q0[b, h * G:(h + 1) * G]), scale, wl.r, wl.w, params,
+                               wl.dtype, n_recent=wl.n_recent, k_candidate=wl.n_candidate,
+                               n_cap=wl.context + 2, acc_dtype=np.float32)
+    st.compress()
+    st = O.compact(st, wl.n_retained + 1)
+    t0 = time.perf_counter()
+    st.decode_step(f64(kn[b, h]), f64(vn[b, h]), f64(q1[b, h * G:(h + 1) * G]), scale)
+    t1 = time.perf_counter()
+    return t0, t1
+
+
+def cpu_baseline(wl, n_units):
+    """Time the oracle's decode step on the host for a few units of the same workload
+    (full shape; building a unit's prompt state is not timed), once with one process
+    per core running side by side and once on a single core, and scale to the whole
+    job.  The oracle is used as it stands: numpy, one unit at a time, one thread each."""
+    import multiprocessing as mp
+
+    cores = max(1, min(16, os.cpu_count() or 1))       # a one-GPU box's share of the host
     total_units = wl.layers * wl.units_per_layer
+    todo = [(wl.name, 0, u // wl.n_kv_heads, u % wl.n_kv_heads) for u in range(min(n_units, wl.units_per_layer))]
+    # one core: the first unit alone
+    t0, t1 = _oracle_unit_step(todo[0])
+    per_unit_1 = t1 - t0
+    # all cores: `cores` workers, one unit each at a time; the figure is unit-steps per second of
+    # wall time while all workers are inside their timed step (mean step time under full load)
+    ctx = mp.get_context("spawn")
+    batch = todo[:cores] if len(todo) >= cores else (todo * cores)[:cores]
+    with ctx.Pool(processes=cores) as pool:
+        spans = pool.map(_oracle_unit_step, batch, chunksize=1)
+    per_unit_all = sum(b - a for a, b in spans) / len(spans)
     return {
-        "value": 1.0 / (per_unit * total_units),
+        "value": cores / (per_unit_all * total_units),
         "unit": "decode steps/s",
-        "cores": 1,
+        "cores": cores,
         "kind": "oracle",
-        "sample": f"{len(times)} unit(s) (layer 0, sequence/head {used[0]}..{used[-1]}) x 1 decode step at full "
-                  f"shape, {per_unit:.3f} s per unit-step, scaled by {total_units} units per step",
+        "value_1core": 1.0 / (per_unit_1 * total_units),
+        "host_cpus_visible": os.cpu_count(),
+        "sample": f"{len(batch)} unit(s) of layer 0 (sequence, head {batch[0][2:]}..{batch[-1][2:]}) x 1 decode step "
+                  f"at full shape, one single-threaded process per core, {cores} side by side: "
+                  f"{per_unit_all:.3f} s per unit-step under load ({per_unit_1:.3f} s alone on one core), scaled by "
+                  f"{total_units} units per step",
     }
 
 
@@ -138,6 +152,12 @@ def main():
                     help="record the HIP event pair around the attention kernels on every n-th launch of the timed "
                          "region (the two event records cost about 10 us per launch they bracket; 5 does not "
                          "divide the layer count, so every layer is sampled)")
+    ap.add_argument("--slack", type=int, default=0,
+                    help="Slack of Algorithm 3: the Recent part may outgrow its budget by this many tokens, then "
+                         "slack + 1 tokens leave each unit at once (0, the headline configuration: one token in, "
+                         "one out per step)")
+    ap.add_argument("--no-side-stream", action="store_true",
+                    help="do not lend kvr_attend_decode a second stream: its two main kernels run back to back")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=8)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -175,6 +195,7 @@ def main():
     descs, layers = [], []
     n_ctx = torch.zeros(B, dtype=torch.int32, device=dev)
     ws_att = ws_enc = None
+    side = None if args.no_side_stream else kvr.SideStream(dev)
     knew, vnew, qs = [], [], []
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_compress_ms = 0.0
@@ -193,7 +214,8 @@ def main():
         qall = S.queries_many(wll, l, 0, T + 1, device=dev)          # q[0] initialises the scores
         ls, _ = LayerState.from_prefill(d, Kf, Vf, qall[0].contiguous(), n_recent=wll.n_recent,
                                         k_candidate=wll.n_candidate, max_new_tokens=T, ws_attend=ws_att,
-                                        ws_encode=ws_enc, n_ctx=n_ctx, timers=(ev0, ev1))
+                                        ws_encode=ws_enc, n_ctx=n_ctx, timers=(ev0, ev1), slack=args.slack,
+                                        side=side)
         torch.cuda.synchronize()
         t_compress_ms += ev0.elapsed_time(ev1)
         ne = ls.n_evict.min().item()
@@ -224,32 +246,40 @@ def main():
     torch.cuda.synchronize()
 
     # ---- timed region ----------------------------------------------------------
-    hev = HipEvents()
     ev_every = max(1, args.event_every)
-    pairs = [(hev.create(), hev.create()) for _ in range((K_steps * L + ev_every - 1) // ev_every)]
+    pairs = [(kvr.event_create(True), kvr.event_create(True)) for _ in range((K_steps * L + ev_every - 1) // ev_every)]
+
+    def attend_opts(a=None, b=None):
+        if side is not None:
+            return side.opts(a, b)
+        return kvr.kvr_attend_opts(None, None, None, a, b) if a is not None else None
+
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     i = 0
     for t in range(W, T):
         n_ctx.add_(1)
         for l in range(L):
-            if i % ev_every == 0:
-                a, b = pairs[i // ev_every]
-                kvr.kvr_profile_events(a, b)
+            opts = attend_opts(*pairs[i // ev_every]) if i % ev_every == 0 else attend_opts()
             i += 1
-            layers[l].decode_step(knew[l][t], vnew[l][t], qs[l][t], bump_n_ctx=False, **swap_kw)
+            layers[l].decode_step(knew[l][t], vnew[l][t], qs[l][t], bump_n_ctx=False, opts=opts, **swap_kw)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
-    kern_ms = [hev.elapsed_ms(a, b) for a, b in pairs]
+    kern_ms = [kvr.event_elapsed_ms(a, b) for a, b in pairs]
     for a, b in pairs:
-        hev.hip.hipEventDestroy(a)
-        hev.hip.hipEventDestroy(b)
+        kvr.hip().hipEventDestroy(a)
+        kvr.hip().hipEventDestroy(b)
 
-    # sanity of the state after the run: one eviction per unit per step
+    # sanity of the state after the run: every unit could evict what it had to, and what went into
+    # the sketch is what Algorithm 3 sends there (one token per unit per step; with Slack s, s + 1
+    # tokens every s + 1 steps)
+    for ls in layers:
+        ls.check_evictions()
     nv = layers[0].n_vague
-    if nv.min().item() != wl_layers[0].n_vague0 + T or nv.max().item() != wl_layers[0].n_vague0 + T:
-        raise RuntimeError("bookkeeping drifted: n_vague is not a0 + steps")
+    want_nv = wl_layers[0].n_vague0 + (T // (args.slack + 1)) * (args.slack + 1)
+    if nv.min().item() != want_nv or nv.max().item() != want_nv:
+        raise RuntimeError(f"bookkeeping drifted: n_vague is {nv.min().item()}..{nv.max().item()}, expected {want_nv}")
     if not torch.isfinite(layers[-1].out).all():
         raise RuntimeError("non-finite attention output")
 
@@ -263,6 +293,26 @@ def main():
     bytes_step = sum(bytes_layer)
     avg_kern_s = (sum(kern_ms) / len(kern_ms)) * 1e-3
     achieved = bytes_launch / avg_kern_s / 1e9
+    off = OFFLINE_COUNTERS.get(wl.name, {}) if (L == wl.layers and s_ramp == 0.0) else {}
+    alu_obj = None
+    if "alu" in off:
+        c = off["alu"]
+        # lane-operations the staged kernel issues per launch (64 lanes per vector instruction) over the live
+        # duration of the call it dominates
+        lane_ops = c["valu_insts_per_launch"] * 64
+        n_vague_mid = wl.n_vague0 + W + (K_steps + 1) // 2
+        alu_obj = {
+            "bound": "alu", "kernel": c["kernel"], "source": c["file"],
+            "achieved": lane_ops / avg_kern_s / 1e12, "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-ops/s",
+            "frac": lane_ops / avg_kern_s / 1e12 / ALU_PEAK_TLANEOPS,
+            "peak_derivation": "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, no packed math",
+            "valu_busy_alone": c["valu_busy"], "lds_busy_alone": c["lds_busy"],
+            "lds_bank_conflict_share": c["lds_bank_conflict_share"],
+            "valu_insts_per_wave": c["valu_insts_per_launch"] / c["waves_per_launch"],
+            "valu_insts_per_rebuilt_token": c["valu_insts_per_launch"] * 64 / (wl.units_per_layer * n_vague_mid),
+            "note": "instruction counts and busy fractions are off-line counter readings of the kernel running "
+                    "alone (the file gives the command); the duration is this run's",
+        }
     result = {
         "metric": "decode steps/sec (encode+reconstruct+attend, all layers) + achieved HBM GB/s",
         "value": steps_per_s,
@@ -294,21 +344,29 @@ def main():
             "hbm_frac": prompt_bytes_layer / (t_compress_ms / L * 1e-3) / 1e9 / HBM_PEAK_GBS,
         },
         "roofline": {
-            "kernel": "attention over retained + reconstructed tokens of one layer, all units: "
-                      "attend_retained_kernel and attend_vague_staged64_kernel, launched side by side on two "
-                      "streams (HIP events on the caller's stream: before the fork, after the join)",
+            "kernel": "one kvr_attend_decode call = attention over retained + reconstructed tokens of one layer, all "
+                      "units: attend_retained_shared_kernel (streams the retained rows; on the lent side stream) next "
+                      "to attend_vague_staged64_kernel (rebuilds the Vague tokens from the sketch in LDS), then "
+                      "attend_combine_kernel (merge + score accumulation); HIP events on the caller's stream before "
+                      "the first and after the last of them" if wl.name in ("c4",) and side is not None else
+                      "one kvr_attend_decode call (retained-slot kernel, Vague-list kernel, merge kernel of one "
+                      "layer, all units); HIP events on the caller's stream before the first and after the last",
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if L == wl.layers else None,
-            "traffic_unit": "bytes per launch (profiles/attend_pair_c4_hbm_traffic.txt)",
+            "traffic": off.get("traffic") if L == wl.layers else None,
+            "traffic_note": off.get("traffic_note", "not measured for this workload"),
             "algorithmic_bytes_per_launch": bytes_launch,
+            "algorithmic_bytes_note": "retained K,V + sketch K,V + Vague index list + scores read and written + q, out: "
+                                      "all of it moved by the three kernels inside the timed region",
             "avg_launch_ms": avg_kern_s * 1e3,
             "launches_timed": len(kern_ms),
-            "launch_sampling": f"HIP events on every {ev_every}. launch of the timed region",
+            "launch_sampling": f"HIP events on every {ev_every}. call of the timed region",
+            "note": "the call is not HBM-bound: its longest kernel is bound by vector-ALU issue and LDS (roofline_alu)",
         },
+        "roofline_alu": alu_obj,
     }
     if args.multi_q > 0:
         nq = args.multi_q

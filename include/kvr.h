@@ -35,8 +35,11 @@
  *
  * Conventions.
  *   - Every pointer marked "dev" is device memory owned by the caller; the
- *     library never allocates, frees or keeps a pointer after the call returns.
- *     Pointers marked "host" are ordinary host memory.
+ *     library never allocates, frees or keeps a pointer after the call returns,
+ *     and it holds no state of its own between calls: no streams, no events, no
+ *     buffers, no environment variables (the only per-thread datum is the error
+ *     code behind kvr_last_hip_error).  Pointers marked "host" are ordinary host
+ *     memory.
  *   - All arrays are dense, row-major, innermost dimension contiguous, in the
  *     shapes given below, unit-major: X[B, Hkv, ...].  Device pointers must be
  *     16-byte aligned.
@@ -112,6 +115,33 @@ typedef struct kvr_desc {
   uint64_t hash_params[KVR_MAX_ROWS][4];
 } kvr_desc;
 
+/*
+ * What a caller may lend to one kvr_attend_decode call (host memory, plain data;
+ * every field may be NULL, and a NULL kvr_attend_opts* means all NULL).
+ *   side_stream, fork_event, join_event: a second hipStream_t of default priority
+ *       (not `stream` itself) and two hipEvent_t (timing may be disabled), created
+ *       and owned by the caller; all three or none.  With them, and when the call is
+ *       large enough for it to pay (bf16, the Vague list long enough to fill the
+ *       chip twice over), the kernel that streams the retained tokens runs on
+ *       side_stream next to the kernel that rebuilds the Vague tokens on `stream`:
+ *       fork_event is recorded on `stream` and awaited by side_stream, join_event is
+ *       recorded on side_stream and awaited by `stream` before the merge kernel, on
+ *       every path including errors, so the call stays ordered on `stream` and the
+ *       workspace is free when work enqueued after the call runs.  Without them the
+ *       two kernels run back to back on `stream`; results are the same.  The three
+ *       handles must not be used by another call that can run at the same time.
+ *   prof_start, prof_stop: two hipEvent_t with timing enabled, both or none;
+ *       recorded on `stream` right before the call's first and right after its last
+ *       kernel (a measuring aid).
+ */
+typedef struct kvr_attend_opts {
+  void* side_stream;
+  void* fork_event;
+  void* join_event;
+  void* prof_start;
+  void* prof_stop;
+} kvr_attend_opts;
+
 /* Library version string (static storage). */
 const char* kvr_version(void);
 
@@ -119,14 +149,18 @@ const char* kvr_version(void);
 int32_t kvr_last_hip_error(void);
 
 /*
- * Profiling aid.  Arms a pair of hipEvent_t (passed as void*, created by the
- * caller with timing enabled) for the calling thread: the next
- * kvr_attend_decode call records `start` on its stream right before its first
- * kernel and `stop` right after the last kernel that touches token data (the
- * ones that stream the retained tokens and rebuild the Vague ones; the final
- * merge kernel is outside), then disarms them.  NULL, NULL disarms.
+ * Size of the Recent queue after the first branch of Algorithm 3 ("Recent and
+ * Candidate"): r_size is R.size right after the new token was pushed, r_budget
+ * is R.budget.  Only when the queue has outgrown its budget by more than `slack`
+ * tokens do the oldest r_size - r_budget of them leave it (for the Candidate
+ * part), all at once, and the queue is back at r_budget; otherwise it keeps its
+ * size.  The result is the n_recent to pass to kvr_select / kvr_step_update /
+ * kvr_swap_back for this step (tokens outside the queue are Candidates, and
+ * kvr_select moves whatever exceeds k_candidate on to the Vague part: slack + 1
+ * tokens every slack + 1 steps).  slack = 0: one token in, one out per step.
+ * Pure host code.  Returns the new size, or KVR_ERR_INVALID_ARG (negative input).
  */
-int32_t kvr_profile_events(void* start, void* stop);
+int32_t kvr_recent_size(int32_t r_size, int32_t r_budget, int32_t slack);
 
 /*
  * Fill out[r][4] (host) from a seed: a 64-bit LCG x <- x*6364136223846793005 +
@@ -209,6 +243,8 @@ int32_t kvr_select(const kvr_desc* desc, const float* scores, int64_t n_cap,
  *   out_bucket  dev int32 [B, Hkv, cap, r] or NULL: h_i(J) of every listed token
  *   out_sign    dev uint8 [B, Hkv, cap] or NULL: bit i set iff g_i(J) = -1
  *   ws          per kvr_workspace_size(KVR_OP_ENCODE, cap, 0)
+ * Lists of up to 64 tokens per unit (cap <= 64) take any w; longer lists go through
+ * a sort by slot that supports w <= 8192, beyond that KVR_ERR_UNSUPPORTED.
  */
 int32_t kvr_encode(const kvr_desc* desc, const void* k_src, const void* v_src, int32_t src_rows,
                    const int32_t* src_slot, const int32_t* tok_pos, const int32_t* count, int32_t cap,
@@ -219,9 +255,12 @@ int32_t kvr_encode(const kvr_desc* desc, const void* k_src, const void* v_src, i
  * Algorithm 3 for one decode step, in one launch: exactly kvr_append, then
  * kvr_select, then kvr_encode of the tokens that kvr_select listed (read from
  * the retained slots they just left), with the same arguments, the same results
- * and the same bit-reproducible sketch as the three separate calls.  For the
- * decode steady state only: ret_cap <= 8192 and evict_cap <= 64, otherwise
- * KVR_ERR_UNSUPPORTED (compress a prompt with the separate calls).
+ * (also for n_recent = 0, where the token just appended is itself a Candidate)
+ * and the same bit-reproducible sketch as the three separate calls.  Any number
+ * of tokens up to evict_cap may leave a unit in one call (Slack > 0: see
+ * kvr_recent_size).  For the decode steady state only: ret_cap <= 8192 and
+ * evict_cap <= 64, otherwise KVR_ERR_UNSUPPORTED (compress a prompt with the
+ * separate calls).
  */
 int32_t kvr_step_update(const kvr_desc* desc, const void* k_new, const void* v_new, const int32_t* n_ctx,
                         void* k_ret, void* v_ret, int32_t* ret_pos, int32_t ret_cap,
@@ -231,12 +270,11 @@ int32_t kvr_step_update(const kvr_desc* desc, const void* k_new, const void* v_n
                         void* sketch_k, void* sketch_v, void* stream);
 
 /*
- * The swap loop of Algorithm 3 ("Additionally, we set a swap mechanism, allowing
- * tokens in the Vague Part to be swapped back to the Candidate Part"), per unit,
- * at most max_swaps times:
- *     while C.Min_Score() * ReplaceRate < V.Max_Score():
- *         tmp <- V.Query(V.Max_Score_Index());  V.Delete(tmp)
- *         V.Insert(C.Top_Pop());  C.Push(tmp)
+ * The swap loop of Algorithm 3 (its second while-loop), per unit, at most
+ * max_swaps times: as long as the lowest Candidate score times ReplaceRate is
+ * below the highest Vague score, that Vague token is queried from the sketch and
+ * deleted from it, the lowest Candidate is popped and inserted into the sketch,
+ * and the queried estimate takes the Candidate's place.
  * Candidate = occupied slots with ret_pos < n_ctx[b] - n_recent.  C.Min: lowest
  * scores[ret_pos], ties: the later position (the token kvr_select would pop
  * first).  V.Max: highest scores[vague_pos[i]], ties: the earlier position.  The
@@ -288,8 +326,8 @@ int32_t kvr_reconstruct(const kvr_desc* desc, const void* sketch_k, const void* 
  * reconstructed on the fly as in kvr_reconstruct (never written to memory):
  *     p[hq, j] = softmax_j(softmax_scale * q[hq] . k*_j),  out[hq] = sum_j p[hq, j] v*_j
  * and, if scores is not NULL, every token's cumulative score grows by the sum
- * of p over the G q heads of its kv head (Overview: "retain and accumulate the
- * attention scores for each token").
+ * of p over the G q heads of its kv head (Overview, Calculation Phase: the
+ * attention scores are kept and accumulated per token).
  * Slots with ret_pos < 0 are skipped; ret_pos == NULL means slot s holds
  * position s for all ret_cap slots.  n_vague == NULL means no Vague tokens
  * (plain dense decode attention).  A unit with no token at all yields out = 0.
@@ -301,13 +339,14 @@ int32_t kvr_reconstruct(const kvr_desc* desc, const void* sketch_k, const void* 
  *   scores     dev float32 [B, Hkv, n_cap] read and written, or NULL; positions
  *              >= n_cap are not accumulated
  *   ws         per kvr_workspace_size(KVR_OP_ATTEND, ret_cap, vague_cap)
+ *   opts       host, or NULL: see kvr_attend_opts
  */
 int32_t kvr_attend_decode(const kvr_desc* desc, const void* q,
                           const void* k_ret, const void* v_ret, const int32_t* ret_pos, int32_t ret_cap,
                           const void* sketch_k, const void* sketch_v,
                           const int32_t* vague_pos, const int32_t* n_vague, int32_t vague_cap,
                           float* out, float* scores, int64_t n_cap,
-                          void* ws, size_t ws_bytes, void* stream);
+                          void* ws, size_t ws_bytes, const kvr_attend_opts* opts, void* stream);
 
 /*
  * The Calculation Phase for n_q query tokens per sequence at once (a chunk of

@@ -29,7 +29,7 @@ _ERR_NAMES = {-1: "KVR_ERR_INVALID_ARG", -2: "KVR_ERR_UNSUPPORTED",
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvr.so")
 
-EXPORTS = ["kvr_version", "kvr_last_hip_error", "kvr_profile_events", "kvr_hash_params_from_seed", "kvr_hash_host",
+EXPORTS = ["kvr_version", "kvr_last_hip_error", "kvr_recent_size", "kvr_hash_params_from_seed", "kvr_hash_host",
            "kvr_workspace_size", "kvr_append", "kvr_select", "kvr_encode", "kvr_step_update",
            "kvr_swap_back", "kvr_reconstruct", "kvr_attend_decode", "kvr_attend_multi_workspace_size",
            "kvr_attend_multi"]
@@ -49,7 +49,63 @@ class kvr_desc(C.Structure):
                 ("hash_params", (C.c_uint64 * 4) * KVR_MAX_ROWS)]
 
 
+class kvr_attend_opts(C.Structure):
+    _fields_ = [("side_stream", C.c_void_p), ("fork_event", C.c_void_p), ("join_event", C.c_void_p),
+                ("prof_start", C.c_void_p), ("prof_stop", C.c_void_p)]
+
+
 _lib = None
+_hip = None
+
+
+def hip() -> C.CDLL:
+    """The HIP runtime, for the few raw handles the C ABI takes (events)."""
+    global _hip
+    if _hip is None:
+        h = C.CDLL("libamdhip64.so")
+        h.hipEventCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
+        h.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        h.hipEventDestroy.argtypes = [C.c_void_p]
+        _hip = h
+    return _hip
+
+
+def event_create(timing: bool) -> C.c_void_p:
+    ev = C.c_void_p()
+    rc = hip().hipEventCreateWithFlags(C.byref(ev), 0 if timing else 2)      # 2 = hipEventDisableTiming
+    if rc != 0:
+        raise RuntimeError(f"hipEventCreateWithFlags failed: {rc}")
+    return ev
+
+
+def event_elapsed_ms(a, b) -> float:
+    ms = C.c_float()
+    rc = hip().hipEventElapsedTime(C.byref(ms), a, b)
+    if rc != 0:
+        raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+    return ms.value
+
+
+class SideStream:
+    """A second stream (default priority) and the fork / join events that a caller
+    lends to kvr_attend_decode so that its two main kernels can run side by side.
+    Plumbing only.  One object serves any number of calls that are ordered on one
+    stream."""
+
+    def __init__(self, device="cuda"):
+        self.stream = torch.cuda.Stream(device=device)
+        self.fork = event_create(False)
+        self.join = event_create(False)
+
+    def opts(self, prof_start=None, prof_stop=None) -> "kvr_attend_opts":
+        return kvr_attend_opts(self.stream.cuda_stream, self.fork, self.join, prof_start, prof_stop)
+
+    def __del__(self):
+        try:
+            hip().hipEventDestroy(self.fork)
+            hip().hipEventDestroy(self.join)
+        except Exception:
+            pass
 
 
 def lib() -> C.CDLL:
@@ -66,8 +122,8 @@ def lib() -> C.CDLL:
         L.kvr_version.argtypes = []
         L.kvr_last_hip_error.restype = i32
         L.kvr_last_hip_error.argtypes = []
-        L.kvr_profile_events.restype = i32
-        L.kvr_profile_events.argtypes = [vp, vp]
+        L.kvr_recent_size.restype = i32
+        L.kvr_recent_size.argtypes = [i32, i32, i32]
         L.kvr_hash_params_from_seed.restype = i32
         L.kvr_hash_params_from_seed.argtypes = [C.c_uint64, i32, C.POINTER(C.c_uint64)]
         L.kvr_hash_host.restype = i32
@@ -91,7 +147,7 @@ def lib() -> C.CDLL:
         L.kvr_reconstruct.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp]
         L.kvr_attend_decode.restype = i32
         L.kvr_attend_decode.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, i64,
-                                        vp, sz, vp]
+                                        vp, sz, C.POINTER(kvr_attend_opts), vp]
         L.kvr_attend_multi_workspace_size.restype = i32
         L.kvr_attend_multi_workspace_size.argtypes = [dp, i32, i64, i64, C.POINTER(sz)]
         L.kvr_attend_multi.restype = i32
@@ -172,9 +228,11 @@ def kvr_version() -> str:
     return lib().kvr_version().decode()
 
 
-def kvr_profile_events(start, stop):
-    """start, stop: raw hipEvent_t handles (ints) or None."""
-    _check("kvr_profile_events", lib().kvr_profile_events(start, stop))
+def kvr_recent_size(r_size: int, r_budget: int, slack: int) -> int:
+    rc = lib().kvr_recent_size(r_size, r_budget, slack)
+    if rc < 0:
+        raise KvrError("kvr_recent_size", rc)
+    return int(rc)
 
 
 def kvr_hash_params_from_seed(seed: int, r: int):
@@ -290,7 +348,7 @@ def kvr_reconstruct(desc, sketch_k, sketch_v, tok_pos, count, cap, k_out, v_out)
 
 
 def kvr_attend_decode(desc, q, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_v, vague_pos, n_vague,
-                      vague_cap, out, scores, n_cap, ws):
+                      vague_cap, out, scores, n_cap, ws, opts=None):
     U, D, dt = desc.batch * desc.n_kv_heads, desc.head_dim, _torch_dtype(desc)
     S = desc.r * desc.w * D
     wp, wb = _ws(ws)
@@ -302,7 +360,8 @@ def kvr_attend_decode(desc, q, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_
         _ptr(vague_pos, torch.int32, U * vague_cap, "vague_pos", True),
         _ptr(n_vague, torch.int32, U, "n_vague", True), vague_cap,
         _ptr(out, torch.float32, desc.batch * desc.n_q_heads * D, "out"),
-        _ptr(scores, torch.float32, U * n_cap, "scores", True), n_cap, wp, wb, _stream())
+        _ptr(scores, torch.float32, U * n_cap, "scores", True), n_cap, wp, wb,
+        C.byref(opts) if opts is not None else None, _stream())
     _check("kvr_attend_decode", rc)
 
 

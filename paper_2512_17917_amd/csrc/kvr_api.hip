@@ -8,7 +8,6 @@
 namespace {
 
 thread_local int32_t g_last_hip_error = 0;
-thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 constexpr uint64_t LCG_MUL = 6364136223846793005ull;
 constexpr uint64_t LCG_INC = 1442695040888963407ull;
@@ -59,10 +58,9 @@ const char* kvr_version(void) { return "kvr 0.1 (gfx950)"; }
 
 int32_t kvr_last_hip_error(void) { return g_last_hip_error; }
 
-int32_t kvr_profile_events(void* start, void* stop) {
-  g_ev_start = (hipEvent_t)start;
-  g_ev_stop = (hipEvent_t)stop;
-  return KVR_OK;
+int32_t kvr_recent_size(int32_t r_size, int32_t r_budget, int32_t slack) {
+  if (r_size < 0 || r_budget < 0 || slack < 0) return KVR_ERR_INVALID_ARG;
+  return ((long long)r_size > (long long)r_budget + slack) ? r_budget : r_size;
 }
 
 int32_t kvr_hash_params_from_seed(uint64_t seed, int32_t r, uint64_t* out) {
@@ -229,15 +227,27 @@ int32_t kvr_reconstruct(const kvr_desc* desc, const void* sketch_k, const void* 
                                         v_out, (hipStream_t)stream));
 }
 
-int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret, const void* v_ret,
+static int32_t attend_decode_common(const kvr_desc* desc, const void* q, const void* k_ret, const void* v_ret,
                           const int32_t* ret_pos, int32_t ret_cap, const void* sketch_k,
                           const void* sketch_v, const int32_t* vague_pos, const int32_t* n_vague,
                           int32_t vague_cap, float* out, float* scores, int64_t n_cap, void* ws,
-                          size_t ws_bytes, void* stream) {
+                          size_t ws_bytes, const kvr_attend_opts* opts, void* stream) {
   kvr::DevDesc d;
   const int32_t rc = check_desc(desc, d);
   if (rc != KVR_OK) return rc;
   if (!q || !k_ret || !v_ret || !out) return KVR_ERR_INVALID_ARG;
+  kvr::AttendSide sd = {nullptr, nullptr, nullptr, nullptr, nullptr};
+  if (opts != nullptr) {
+    const int n_side = (opts->side_stream != nullptr) + (opts->fork_event != nullptr) + (opts->join_event != nullptr);
+    if (n_side != 0 && n_side != 3) return KVR_ERR_INVALID_ARG;
+    if ((opts->prof_start == nullptr) != (opts->prof_stop == nullptr)) return KVR_ERR_INVALID_ARG;
+    if (opts->side_stream != nullptr && opts->side_stream == stream) return KVR_ERR_INVALID_ARG;
+    sd.stream = (hipStream_t)opts->side_stream;
+    sd.fork = (hipEvent_t)opts->fork_event;
+    sd.join = (hipEvent_t)opts->join_event;
+    sd.prof_start = (hipEvent_t)opts->prof_start;
+    sd.prof_stop = (hipEvent_t)opts->prof_stop;
+  }
   if ((vague_pos == nullptr) != (n_vague == nullptr)) return KVR_ERR_INVALID_ARG;
   if (n_vague != nullptr && (!sketch_k || !sketch_v)) return KVR_ERR_INVALID_ARG;
   if (ret_cap < 1 || ret_cap > MAX_TOKENS) return KVR_ERR_INVALID_ARG;
@@ -272,9 +282,16 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret
   a.scratch_rec = plan.streamed ? (void*)(base + plan.off_rec) : nullptr;
   a.scratch_partial = plan.streamed ? (void*)(base + plan.off_partial) : nullptr;
   a.n_q = 1;
-  const hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;
-  g_ev_start = g_ev_stop = nullptr;
-  return finish(kvr::launch_attend(d, desc->dtype, a, plan, (hipStream_t)stream, e0, e1));
+  return finish(kvr::launch_attend(d, desc->dtype, a, plan, (hipStream_t)stream, sd));
+}
+
+int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret, const void* v_ret,
+                          const int32_t* ret_pos, int32_t ret_cap, const void* sketch_k,
+                          const void* sketch_v, const int32_t* vague_pos, const int32_t* n_vague,
+                          int32_t vague_cap, float* out, float* scores, int64_t n_cap, void* ws,
+                          size_t ws_bytes, const kvr_attend_opts* opts, void* stream) {
+  return attend_decode_common(desc, q, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_v, vague_pos, n_vague,
+                              vague_cap, out, scores, n_cap, ws, ws_bytes, opts, stream);
 }
 
 static int32_t check_multi(const kvr_desc* desc, kvr::DevDesc& d, int32_t n_q) {

@@ -13,8 +13,6 @@
 // sign setting; Vague rows gathered straight from global memory), the merge
 // kernel and the dispatch.  The LDS-staged kernel for the Vague list is in
 // kvr_attend_staged.hip.
-#include <stdlib.h>
-
 #include "kvr_launch.h"
 
 namespace kvr {
@@ -441,47 +439,13 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
 }
 
 // ---------------------------------------------------------------------------
-// Side stream for running the retained kernel next to the staged kernel.  One
-// per host thread, created on first use (default priority, non-blocking), kept
-// until the process ends.  KVR_NO_OVERLAP=1 in the environment switches the
-// overlap off (both kernels then run back to back on the caller's stream).
-struct SideStream {
-  hipStream_t stream;
-  hipEvent_t fork, join;
-};
-
-static bool overlap_enabled() {
-  static const bool on = []() {
-    const char* v = getenv("KVR_NO_OVERLAP");
-    return !(v != nullptr && v[0] == '1');
-  }();
-  return on;
-}
-
+// compute units of the current device (the runtime answers from its own tables; nothing is cached here)
 static int cu_count() {
-  static const int n = []() {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-      cus = 256;
-    return cus;
-  }();
-  return n;
-}
-
-static SideStream* side_stream() {
-  thread_local SideStream s = {nullptr, nullptr, nullptr};
-  thread_local int state = 0;        // 0 = not tried, 1 = ready, -1 = failed
-  if (state == 0) {
-    state = -1;
-    if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
-        hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
-        hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess)
-      state = 1;
-    else
-      (void)hipGetLastError();
-  }
-  return state == 1 ? &s : nullptr;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
+  return cus;
 }
 
 template <typename T, int G>
@@ -512,35 +476,45 @@ hipError_t launch_attend_combine(const DevDesc& d, const AttendArgs& a, int n_co
 
 template <int G>
 static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, const AttendPlan& plan,
-                           hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                           hipStream_t st, const AttendSide& sd) {
   const int units = d.B * d.Hkv;
   AttendArgs a = a0;
   a.n_slices = plan.n_slices;
   a.n_rslices = plan.n_rslices;
   a.n_vslices = plan.n_vslices;
-  if (ev_start) (void)hipEventRecord(ev_start, st);
+  if (sd.prof_start) (void)hipEventRecord(sd.prof_start, st);
   hipError_t e = hipSuccess;
   // 1. retained slots (or, for f32 storage without staging, everything at once)
   a.slice_tokens = plan.rslice_tokens;
   a.tok_start = 0;
   a.slice0 = 0;
   // The retained kernel is bound by HBM, the staged kernel by the vector ALUs and
-  // LDS, and their registers and LDS fit on a CU together: run them side by side,
-  // the retained kernel on a side stream forked from and joined back into `st`.
+  // LDS, and their registers and LDS fit on a CU together: when the caller lends a
+  // second stream they run side by side, the retained kernel on that stream, forked
+  // from and joined back into `st` with the caller's two events.
   // Only when the staged kernel fills the chip several times over: a launch of a few workgroups is
   // short, the fork and join then cost more than the overlap saves, and the retained kernel is better
   // off with a launch as wide as its item count than with one workgroup per CU.
-  const bool big = (long long)units * plan.n_vslices >= 2ll * cu_count();
-  SideStream* side = (plan.mfma_retained && plan.staged && big && overlap_enabled()) ? side_stream() : nullptr;
-  if (side != nullptr) {
-    e = hipEventRecord(side->fork, st);
-    if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
-    const bool s64 = d.r == 3 && plan.ch == 64 && 3 * d.w <= 1024;          // the 64-channel staged kernel runs
-    const int reg_form = s64 ? 1 : ((d.G == 4 && plan.ch <= 16) ? 2 : 0);
-    if (e == hipSuccess) e = launch_attend_retained(d, a, plan.n_rslices, cu_count(), reg_form, side->stream);
-    if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
-    if (e == hipSuccess) e = launch_attend_vague_staged(d, a, plan, st);
-    if (e == hipSuccess) e = hipStreamWaitEvent(st, side->join, 0);
+  const int cus = cu_count();
+  const bool big = (long long)units * plan.n_vslices >= 2ll * cus;
+  const bool side = sd.stream != nullptr && plan.mfma_retained && plan.staged && big;
+  if (side) {
+    e = hipEventRecord(sd.fork, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(sd.stream, sd.fork, 0);
+    if (e == hipSuccess) {
+      // From here on the side stream may hold work that writes the caller's workspace: whatever
+      // fails below, `st` is made to wait for it before this call returns.
+      const bool s64 = d.r == 3 && plan.ch == 64 && 3 * d.w <= 1024;          // the 64-channel staged kernel runs
+      const int reg_form = s64 ? 1 : ((d.G == 4 && plan.ch <= 16) ? 2 : 0);
+      e = launch_attend_retained(d, a, plan.n_rslices, cus, reg_form, sd.stream);
+      const hipError_t ej = hipEventRecord(sd.join, sd.stream);
+      if (e == hipSuccess && ej == hipSuccess) e = launch_attend_vague_staged(d, a, plan, st);
+      hipError_t ew = (ej == hipSuccess) ? hipStreamWaitEvent(st, sd.join, 0) : ej;
+      if (ew != hipSuccess) {
+        (void)hipStreamSynchronize(sd.stream);      // no event to order by: wait on the host (error path only)
+        if (e == hipSuccess) e = ew;
+      }
+    }
   } else if (plan.mfma_retained) {
     e = launch_attend_retained(d, a, plan.n_rslices, 0, 0, st);
   } else {
@@ -551,7 +525,7 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
     e = hipGetLastError();
   }
   // 2. the Vague list
-  if (side != nullptr) {
+  if (side) {
     // already launched above
   } else if (e == hipSuccess && plan.staged) {
     e = launch_attend_vague_staged(d, a, plan, st);
@@ -569,18 +543,19 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
     launch_main_r<bf16_t, G>(d, a, grid, st);
     e = hipGetLastError();
   }
-  if (ev_stop) (void)hipEventRecord(ev_stop, st);
-  if (e != hipSuccess) return e;
-  return launch_attend_combine(d, a, G, st);
+  // 3. merge
+  if (e == hipSuccess) e = launch_attend_combine(d, a, G, st);
+  if (sd.prof_stop) (void)hipEventRecord(sd.prof_stop, st);
+  return e;
 }
 
 hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, const AttendPlan& plan,
-                         hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                         hipStream_t st, const AttendSide& sd) {
   switch (d.G) {
-    case 1: return launch_g<1>(d, dtype, a, plan, st, ev_start, ev_stop);
-    case 2: return launch_g<2>(d, dtype, a, plan, st, ev_start, ev_stop);
-    case 4: return launch_g<4>(d, dtype, a, plan, st, ev_start, ev_stop);
-    case 8: return launch_g<8>(d, dtype, a, plan, st, ev_start, ev_stop);
+    case 1: return launch_g<1>(d, dtype, a, plan, st, sd);
+    case 2: return launch_g<2>(d, dtype, a, plan, st, sd);
+    case 4: return launch_g<4>(d, dtype, a, plan, st, sd);
+    case 8: return launch_g<8>(d, dtype, a, plan, st, sd);
     default: return hipErrorInvalidValue;
   }
 }

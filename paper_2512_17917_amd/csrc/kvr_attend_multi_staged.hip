@@ -98,24 +98,6 @@ __device__ __forceinline__ void stage_issue_swz(const unsigned char* __restrict_
   }
 }
 
-// Development aid, compiled out unless KVR_PHASE_TIMING is defined: lane 0 of every wave stamps the cycle
-// counter at phase boundaries.
-#ifdef KVR_PHASE_TIMING
-__device__ unsigned long long g_ms_phase_t[512 * MS_WAVES * 8];
-#define KVR_MS_STAMP(i)                                                                  \
-  do {                                                                                   \
-    if ((threadIdx.x & 63) == 0 && blockIdx.x < 512)                                     \
-      g_ms_phase_t[(blockIdx.x * MS_WAVES + (threadIdx.x >> 6)) * 8 + (i)] = clock64();  \
-  } while (0)
-extern "C" int kvr_debug_ms_phase_times(unsigned long long* host_out, int n_words) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_ms_phase_t), (size_t)n_words * 8, 0, hipMemcpyDeviceToHost);
-}
-#else
-#define KVR_MS_STAMP(i) \
-  do {                  \
-  } while (0)
-#endif
-
 template <int NCOL>
 __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc d, MultiStagedArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -165,7 +147,6 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
     return __builtin_amdgcn_readfirstlane(t);
   };
 
-  KVR_MS_STAMP(0);
   // ---- K phases -----------------------------------------------------------------------------------
   float m_run = NEG_INF;
   for (int cc = 0; cc < 2; ++cc) {
@@ -258,14 +239,8 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
         const uint4 x0 = *reinterpret_cast<const uint4*>(s_sk + swz_piece(rb[0], p));
         const uint4 x1 = *reinterpret_cast<const uint4*>(s_sk + swz_piece(rb[1], p));
         const uint4 x2 = *reinterpret_cast<const uint4*>(s_sk + swz_piece(rb[2], p));
-        ka[kx] = make_uint4(med3_bf16x2(x0.x, x1.x, x2.x), med3_bf16x2(x0.y, x1.y, x2.y),
-                            med3_bf16x2(x0.z, x1.z, x2.z), med3_bf16x2(x0.w, x1.w, x2.w));
+        ka[kx] = med3_piece(x0, x1, x2);
       }
-      // The medians come out of inline assembly, whose register writes the compiler's hazard logic does
-      // not treat as vector-ALU writes in front of a matrix instruction: keep them well apart.
-      __builtin_amdgcn_sched_barrier(0);
-      asm volatile("s_nop 7\n\ts_nop 7");
-      __builtin_amdgcn_sched_barrier(0);
       f32x4_t S = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kx = 0; kx < 2; ++kx)
@@ -296,7 +271,6 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
       ti = t2;
     }
     k_stores();
-    KVR_MS_STAMP(1 + cc);
   }
   // the wave's maximum per column (the four 16-lane rows hold different tokens of the same column)
   m_run = fmaxf(m_run, __shfl_xor(m_run, 16));
@@ -377,7 +351,7 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
         const uint32_t fm = (uint32_t)((int)rj[j].y >> 31) & 0x80008000u;
         x2.x ^= fm;
         x2.y ^= fm;
-        vt[j] = make_uint2(med3_bf16x2(x0.x, x1.x, x2.x), med3_bf16x2(x0.y, x1.y, x2.y));
+        vt[j] = med3_half_piece(x0, x1, x2);
       }
       short4_t bop[4];
       bop[0] = pack_k4(pair_lo(vt[0].x, vt[1].x), pair_lo(vt[2].x, vt[3].x));
@@ -399,7 +373,6 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
       v_tile(in_b, in_a, t1, t2);
       ti = t2;
     }
-    KVR_MS_STAMP(3 + 2 * cc);
     if (cc == 0) {
       // a lane's sum of weights covers its own four tokens of every tile: add the four 16-lane rows
       float l = l_run + __shfl_xor(l_run, 16);
@@ -434,7 +407,6 @@ __global__ __launch_bounds__(MS_THREADS) void attend_multi_staged_kernel(DevDesc
         a.part_ml[(part * NCOL + c_) * 2 + 1] = L;
       }
     }
-    KVR_MS_STAMP(4 + 2 * cc);
   }
 }
 
@@ -456,14 +428,14 @@ int multi_staged_part_tokens(long long vague_cap, long long units) {
 
 template <int NCOL>
 static hipError_t launch_n(const DevDesc& d, const MultiStagedArgs& a, hipStream_t st) {
-  static bool attr_set = false;
   auto kern = attend_multi_staged_kernel<NCOL>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::once_flag once;
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(once, [&]() {
+    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  160 * 1024);
+  });
+  if (attr_rc != hipSuccess) return attr_rc;
   size_t chunk = ((size_t)3 * d.w * 128 + 1023) & ~(size_t)1023;
   const size_t merge = (size_t)MS_WAVES * NCOL * 64 * 4;
   if (chunk < merge) chunk = merge;

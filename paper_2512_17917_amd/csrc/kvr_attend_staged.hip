@@ -106,7 +106,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
     info[k] = pk;
     s_info[(k * ST_WAVES + wave) * 64 + lane] = pk;
   }
-  if (touched == 0x7fc1u && nv < 0) vmask = 0;       // never true; keeps the touch load alive
+  asm volatile("" ::"v"(touched));       // the touch load has no other use: keep it
   if (tid < G * 16) {
     const uint4* qg = reinterpret_cast<const uint4*>((const bf16_t*)a.q + ((size_t)b * d.Hq + (size_t)hk * G) * D);
     s_q[tid] = qg[tid];
@@ -394,14 +394,14 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_kernel(DevDesc
 
 template <int G, int R, int CH, int MODE>
 static hipError_t launch_one(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
-  static bool attr_set = false;
   auto kern = attend_vague_staged_kernel<G, R, CH, MODE>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::once_flag once;
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(once, [&]() {
+    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  160 * 1024);
+  });
+  if (attr_rc != hipSuccess) return attr_rc;
   const int units = d.B * d.Hkv;
   const int units_pad = (units + 7) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3(units_pad * plan.n_vslices), dim3(ST_THREADS), plan.lds_bytes, st, d, a);

@@ -21,40 +21,6 @@
 
 namespace kvr {
 
-// Development aid, compiled out unless KVR_PHASE_TIMING is defined: lane 0 of
-// every wave stamps the cycle counter at phase boundaries.
-#ifdef KVR_PHASE_TIMING
-__device__ unsigned long long g_phase_t[2048 * 8 * 16];
-#define KVR_STAMP(i)                                                              \
-  do {                                                                            \
-    if ((threadIdx.x & 63) == 0 && blockIdx.x < 2048)                             \
-      g_phase_t[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (i)] = clock64();    \
-  } while (0)
-// wall clock (100 MHz, the same on every CU) and the hardware ids of the wave's CU
-#define KVR_WSTAMP(i)                                                                   \
-  do {                                                                                  \
-    if ((threadIdx.x & 63) == 0 && blockIdx.x < 2048)                                   \
-      g_phase_t[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (i)] = wall_clock64();     \
-  } while (0)
-#define KVR_IDSTAMP(i)                                                                  \
-  do {                                                                                  \
-    if ((threadIdx.x & 63) == 0 && blockIdx.x < 2048)                                   \
-      g_phase_t[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 16 + (i)] =                     \
-          (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |               \
-          ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);       \
-  } while (0)
-#else
-#define KVR_STAMP(i) \
-  do {               \
-  } while (0)
-#define KVR_WSTAMP(i) \
-  do {                \
-  } while (0)
-#define KVR_IDSTAMP(i) \
-  do {                 \
-  } while (0)
-#endif
-
 struct Rows3 {
   uint4 r0, r1, r2;
 };
@@ -66,8 +32,7 @@ __device__ __forceinline__ void load_rows3(Rows3& o, const unsigned char* s_sk, 
 }
 
 __device__ __forceinline__ uint4 median3(const Rows3& x) {
-  return make_uint4(med3_bf16x2(x.r0.x, x.r1.x, x.r2.x), med3_bf16x2(x.r0.y, x.r1.y, x.r2.y),
-                    med3_bf16x2(x.r0.z, x.r1.z, x.r2.z), med3_bf16x2(x.r0.w, x.r1.w, x.r2.w));
+  return med3_piece(x.r0, x.r1, x.r2);
 }
 
 // value of lane J of this lane's quad
@@ -221,10 +186,6 @@ __device__ __forceinline__ void k_pass(const unsigned char* s_sk, const uint2 (&
   // Three-stage pipeline over the steps t = 8 k + j of all rounds: at step t the
   // rows of step t + 3 are requested, the medians of step t + 1 are formed, and
   // the matrix instructions of step t run on medians formed one step earlier.
-  // (The medians come out of inline assembly, whose register writes the
-  // compiler's hazard logic does not see as vector-ALU writes: a matrix
-  // instruction right behind them read a stale operand.  Here at least a whole
-  // step lies between the two.)
   Rows3 buf[3];                          // rows of step t live in buf[t % 3]
   int rb[3];
   rec_offsets(opaque(info[0]), 0, rb);
@@ -354,9 +315,6 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(96))) vo
   const unsigned char* svg = reinterpret_cast<const unsigned char*>((const bf16_t*)a.sv + sk_unit);
   const int n_pieces = R * w * NC;
 
-  KVR_STAMP(0);
-  KVR_WSTAMP(12);
-  KVR_IDSTAMP(14);
   __builtin_amdgcn_s_setprio(1);
   // ---- loads first: Vague positions of this wave's tokens, q, and a touch of
   //      this workgroup's share of the unit's two sketches (so that the later
@@ -420,9 +378,8 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(96))) vo
     }
     info[k] = pk;
   }
-  if (touched == 0x7fc1u && nv < 0) vmask = 0;       // never true; keeps the touch load alive
+  asm volatile("" ::"v"(touched));       // the touch load has no other use: keep it
   if (tid < G * 16) s_q[tid] = qv;
-  KVR_STAMP(1);
   stage_wait();
   lds_barrier();
 
@@ -440,7 +397,6 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(96))) vo
       stage_wait();
       lds_barrier();
     }
-    KVR_STAMP(2 + 2 * cc);
     {
       const int head = lane & 3, pair = lane >> 1, blk2 = (lane >> 2) * 2;
       uint4 qx[8];
@@ -453,7 +409,6 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(96))) vo
       const bool second_pair = (lane & 2) != 0;
       KVR_DISPATCH_NK(n_k, (k_pass<NK, G>(s_sk, info, qx, co, second_pair, turn, s)))
     }
-    KVR_STAMP(3 + 2 * cc);
   }
 
   // ---- the first V chunk is on its way during the softmax ----------------------
@@ -557,7 +512,6 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(96))) vo
   }
 
   // ---- V phases: weighted values ------------------------------------------------
-  KVR_STAMP(6);
   // the two pieces of this lane: odd quads take them in the opposite order, so
   // that 8 neighbouring lanes always cover 8 different 16-byte bank groups
   const int pa = sub + ((tl & 1) ? 4 : 0);
@@ -567,7 +521,6 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(96))) vo
   for (int cc = 0; cc < NPH; ++cc) {
     stage_wait();
     lds_barrier();
-    KVR_STAMP(7 + 2 * cc);
     if (cc == 0) {
       // every wave's maximum and row sums are visible now (this wave's own maximum is
       // read back too: it would not survive in registers without being spilled)
@@ -615,7 +568,6 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(96))) vo
 #pragma unroll
       for (int g = 0; g < 4; ++g) acc[c][g] = xchg4(acc[c][g]);
     KVR_DISPATCH_NK(n_k, (v_pass<NK>(s_sk, info, W, pb * 16, turn + 1, acc)))
-    KVR_STAMP(8 + 2 * cc);
     lds_barrier();                         // every wave is done with this V chunk
     if (cc + 1 < NPH) stage_issue<NC, ROWB>(svg, s_sk, n_pieces, cc + 1, tid);
 
@@ -654,26 +606,18 @@ __global__ __launch_bounds__(ST_THREADS) __attribute__((amdgpu_num_vgpr(96))) vo
     // the next iteration's barrier (after its stage_wait) orders these reads
     // before the next writes into s_part
   }
-  KVR_STAMP(11);
-  KVR_WSTAMP(13);
 }
-
-#ifdef KVR_PHASE_TIMING
-extern "C" int kvr_debug_phase_times(unsigned long long* host_out, int n_words) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_phase_t), (size_t)n_words * 8, 0, hipMemcpyDeviceToHost);
-}
-#endif
 
 template <int G>
 static hipError_t launch64(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
-  static bool attr_set = false;
   auto kern = attend_vague_staged64_kernel<G>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::once_flag once;
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(once, [&]() {
+    attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  160 * 1024);
+  });
+  if (attr_rc != hipSuccess) return attr_rc;
   const int units = d.B * d.Hkv;
   const int units_pad = (units + 7) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3(units_pad * plan.n_vslices), dim3(ST_THREADS), plan.lds_bytes, st, d, a);

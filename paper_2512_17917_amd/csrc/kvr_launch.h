@@ -4,6 +4,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "kvr_dev.h"
 
 namespace kvr {
@@ -75,11 +77,16 @@ hipError_t launch_reconstruct(const DevDesc& d, int dtype, const void* sk, const
                               const int32_t* tok_pos, const int32_t* count, int cap,
                               void* k_out, void* v_out, hipStream_t st);
 
-// ev_start / ev_stop (may be null): recorded on `st` right before the first and
-// right after the last kernel that touches token data (everything except the
-// merge kernel), for profiling.
+// What the caller of kvr_attend_decode lends to a call (all may be null): a second stream with a fork and a
+// join event for running the retained-slot kernel next to the staged kernel, and two events that are
+// recorded on `st` right before the call's first and right after its last kernel.
+struct AttendSide {
+  hipStream_t stream;
+  hipEvent_t fork, join;
+  hipEvent_t prof_start, prof_stop;
+};
 hipError_t launch_attend(const DevDesc& d, int dtype, const AttendArgs& a, const AttendPlan& plan,
-                         hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
+                         hipStream_t st, const AttendSide& sd);
 
 // tokens per slice when `tokens` tokens of each of `units` units are cut for about 1280 workgroups
 int attend_slice_tokens(long long tokens, long long units);

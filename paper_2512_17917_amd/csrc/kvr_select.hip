@@ -86,8 +86,8 @@ __global__ __launch_bounds__(SEL_THREADS) void step_update_kernel(
     T* __restrict__ sk, T* __restrict__ sv) {
   const int unit = blockIdx.x;
   // the slot positions are read once and serve both the search for a free slot and
-  // the selection keys (the token appended in between is Recent: for the selection
-  // its slot might as well still be empty)
+  // the selection keys (the token appended in between is Recent unless n_recent = 0:
+  // for the selection its slot might as well still be empty)
   int pre[SEL_KPT];
   {
     const int32_t* rp = ret_pos + (size_t)unit * ret_cap;
@@ -116,8 +116,19 @@ __global__ __launch_bounds__(SEL_THREADS) void step_update_kernel(
       pre_sc[j] = (pos >= 0 && pos < recent_from && pos < n_cap) ? sc[pos] : 0.f;
     }
   }
-  (void)append_body_pre<T, SEL_THREADS, SEL_KPT>(d, unit, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap, pre,
-                                                 &row_in);
+  const int s_new = append_body_pre<T, SEL_THREADS, SEL_KPT>(d, unit, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos,
+                                                             ret_cap, pre, &row_in);
+  if (n_recent == 0 && s_new >= 0) {
+    // an empty Recent window: the token just appended is a Candidate like any other, so the
+    // thread that holds its slot ranks it by its real position instead of the stale "empty"
+    const int pos_new = n_ctx[unit / d.Hkv] - 1;
+#pragma unroll
+    for (int j = 0; j < SEL_KPT; ++j)
+      if (j * SEL_THREADS + (int)threadIdx.x == s_new) {
+        pre[j] = pos_new;
+        pre_sc[j] = (pos_new >= 0 && pos_new < n_cap) ? scores[(size_t)unit * n_cap + pos_new] : 0.f;
+      }
+  }
   __syncthreads();          // the new row and its ret_pos entry are visible to the whole workgroup
   select_body<true>(d, unit, scores, n_cap, ret_pos, ret_cap, n_ctx, n_recent, k_cand, evict_slot, evict_pos,
                     n_evict, evict_cap, vague_pos, n_vague, vague_cap, pre, pre_sc);

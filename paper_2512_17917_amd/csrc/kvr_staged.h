@@ -10,11 +10,36 @@ constexpr int ST_KMAX = 6;
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ uint32_t med3_bf16x2(uint32_t a, uint32_t b, uint32_t c) {
+// Per-channel median of three on packed bf16, taken on the raw bit patterns with
+// v_med3_f16 (bf16 and f16 are both sign-magnitude with the exponent above the
+// mantissa, so finite values order the same way; zeros of either sign compare
+// equal).  The low and the high halves are two instructions: the first writes the
+// low 16 bits of the destination, the second (op_sel) the high 16 bits and leaves
+// the low half as it is.
+//
+// These are inline assembly, and the compiler's hazard bookkeeping does not see
+// the register writes of inline assembly as vector-ALU writes: it would place a
+// matrix instruction that reads the result directly behind it, which needs two
+// wait states after a vector-ALU write on this target.  The wait states are
+// therefore part of the primitive (s_nop 1 = two wait states behind the write
+// that completes the dword), and the result may be consumed by any instruction
+// right away: nothing depends on how the surrounding code is scheduled.  (Forms
+// with one s_nop per 16-byte piece were measured: they tie up more registers at
+// once, which costs the widest kernel more than the three s_nop they save.)
+__device__ __forceinline__ uint32_t med3_dword(uint32_t a, uint32_t b, uint32_t c) {
   uint32_t dst;
   asm("v_med3_f16 %0, %1, %2, %3" : "=v"(dst) : "v"(a), "v"(b), "v"(c));
-  asm("v_med3_f16 %0, %1, %2, %3 op_sel:[1,1,1,1]" : "+v"(dst) : "v"(a), "v"(b), "v"(c));
+  asm("v_med3_f16 %0, %1, %2, %3 op_sel:[1,1,1,1]\n\ts_nop 1" : "+v"(dst) : "v"(a), "v"(b), "v"(c));
   return dst;
+}
+// 8 bytes (4 channels)
+__device__ __forceinline__ uint2 med3_half_piece(uint2 a, uint2 b, uint2 c) {
+  return make_uint2(med3_dword(a.x, b.x, c.x), med3_dword(a.y, b.y, c.y));
+}
+// 16 bytes (8 channels)
+__device__ __forceinline__ uint4 med3_piece(uint4 a, uint4 b, uint4 c) {
+  return make_uint4(med3_dword(a.x, b.x, c.x), med3_dword(a.y, b.y, c.y), med3_dword(a.z, b.z, c.z),
+                    med3_dword(a.w, b.w, c.w));
 }
 
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
@@ -31,6 +56,9 @@ __device__ __forceinline__ uint32_t pack_bf16_exact(float lo, float hi) {
 
 // Packed minimum / maximum of two bf16 pairs on their raw bits (same argument as
 // for v_med3_f16: the order of finite values is the same in both formats).
+// Inline assembly again: results of these two may only feed ordinary vector-ALU
+// instructions (which need no wait states); pk_min_bits_last carries the wait
+// states for any consumer.
 __device__ __forceinline__ uint32_t pk_min_bits(uint32_t a, uint32_t b) {
   uint32_t dst;
   asm("v_pk_min_f16 %0, %1, %2" : "=v"(dst) : "v"(a), "v"(b));
@@ -41,22 +69,27 @@ __device__ __forceinline__ uint32_t pk_max_bits(uint32_t a, uint32_t b) {
   asm("v_pk_max_f16 %0, %1, %2" : "=v"(dst) : "v"(a), "v"(b));
   return dst;
 }
-// two float32 -> packed bf16, round to nearest even (one instruction on gfx950)
-__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+__device__ __forceinline__ uint32_t pk_min_bits_last(uint32_t a, uint32_t b) {
   uint32_t dst;
-  asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(dst) : "v"(lo), "v"(hi));
+  asm("v_pk_min_f16 %0, %1, %2\n\ts_nop 1" : "=v"(dst) : "v"(a), "v"(b));
   return dst;
 }
+// two float32 -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32, emitted by the compiler itself)
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 
+// Median over R rows of one dword (two packed bf16 channels), R != 3.
 template <int R>
 __device__ __forceinline__ uint32_t median_dword(const uint32_t (&x)[R], int mode) {
-  if constexpr (R == 3) {
-    return med3_bf16x2(x[0], x[1], x[2]);
-  } else if constexpr (R == 4) {
+  static_assert(R != 3, "three rows go through med3_piece");
+  if constexpr (R == 4) {
     // the two middle values of four: max of the pair minima, min of the pair maxima
     const uint32_t m1 = pk_max_bits(pk_min_bits(x[0], x[1]), pk_min_bits(x[2], x[3]));
     const uint32_t m2 = pk_min_bits(pk_max_bits(x[0], x[1]), pk_max_bits(x[2], x[3]));
-    if (mode == KVR_MEDIAN_LOWER) return pk_min_bits(m1, m2);
+    if (mode == KVR_MEDIAN_LOWER) return pk_min_bits_last(m1, m2);
     // their mean in float32, rounded once to bf16
     return cvt_pk_bf16(0.5f * (bf_lo(m1) + bf_lo(m2)), 0.5f * (bf_hi(m1) + bf_hi(m2)));
   } else {
@@ -70,11 +103,15 @@ __device__ __forceinline__ uint32_t median_dword(const uint32_t (&x)[R], int mod
 // Median over R rows of a 16-byte piece (8 packed bf16 channels).
 template <int R>
 __device__ __forceinline__ uint4 median_piece(const uint4 (&row)[R], int mode) {
-  uint32_t x[R], y[R], z[R], w_[R];
+  if constexpr (R == 3) {
+    return med3_piece(row[0], row[1], row[2]);
+  } else {
+    uint32_t x[R], y[R], z[R], w_[R];
 #pragma unroll
-  for (int i = 0; i < R; ++i) { x[i] = row[i].x; y[i] = row[i].y; z[i] = row[i].z; w_[i] = row[i].w; }
-  return make_uint4(median_dword<R>(x, mode), median_dword<R>(y, mode), median_dword<R>(z, mode),
-                    median_dword<R>(w_, mode));
+    for (int i = 0; i < R; ++i) { x[i] = row[i].x; y[i] = row[i].y; z[i] = row[i].z; w_[i] = row[i].w; }
+    return make_uint4(median_dword<R>(x, mode), median_dword<R>(y, mode), median_dword<R>(z, mode),
+                      median_dword<R>(w_, mode));
+  }
 }
 
 __device__ __forceinline__ uint4 xor4(uint4 v, uint32_t mask) {

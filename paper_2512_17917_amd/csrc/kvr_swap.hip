@@ -1,8 +1,8 @@
-// kvr_swap_back: the swap loop of Algorithm 3 (Recent and Candidate):
-//
-//     while C.Min_Score() * ReplaceRate < V.Max_Score():
-//         tmp <- V.Query(V.Max_Score_Index());  V.Delete(tmp)
-//         V.Insert(C.Top_Pop());                C.Push(tmp)
+// kvr_swap_back: the swap loop of Algorithm 3 (Recent and Candidate; its second
+// while-loop): as long as the weakest Candidate's score times ReplaceRate is below
+// the strongest Vague token's score, that Vague token is queried from the sketch
+// and deleted from it, the Candidate is popped and inserted into the sketch, and
+// the queried estimate is pushed into the Candidate part in its place.
 //
 // One workgroup per unit, at most max_swaps rounds.
 //
@@ -14,7 +14,7 @@
 // key of the retained slots outside the Recent window.
 //
 // One scan serves many rounds.  The keys are loaded once (REG: into registers, up
-// to 32 Vague tokens and 8 slots per thread; otherwise they are re-read from
+// to 26 Vague tokens and 8 slots per thread; otherwise they are re-read from
 // memory), and the m = min(max_swaps, 16) largest Vague keys and m smallest
 // Candidate keys are extracted by m workgroup-wide reductions into two sorted
 // lists in LDS.  A swap pops both heads and inserts each token's key into the

@@ -214,9 +214,10 @@ __device__ __forceinline__ void pick_digit(SelShared& sh, int byte) {
 // in registers (KPT per thread: 8 for the retained slots of a decode step, 32 for
 // a 32k prompt).  Writes the eviction lists, frees the slots, appends to the Vague
 // list, sets n_evict (negative = needed count on overflow, nothing evicted).
-// pre (REG only, may be null): positions of this thread's slots as they were
-// before a token was appended in this same launch; the appended token is Recent
-// and therefore ranks like an empty slot, so the stale value serves.
+// pre (REG only, may be null): positions of this thread's slots, read by the caller
+// ahead of time.  The fused update kernel reads them before it appends the new
+// token: while that token is Recent it ranks like an empty slot, so the stale
+// value serves; with an empty Recent window the kernel patches the one entry.
 // pre_sc (with pre, may be null): the scores at those positions, gathered by the
 // caller ahead of time (valid where the position is eligible).
 template <bool REG, int KPT = SEL_KPT>

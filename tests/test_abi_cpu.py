@@ -32,6 +32,20 @@ def test_desc_layout_matches_header():
     # 9 int32 + 1 float = 40 bytes, then 8 x 4 uint64
     assert C.sizeof(kvr.kvr_desc) == 40 + 8 * 4 * 8
     assert kvr.kvr_desc.hash_params.offset == 40
+    assert C.sizeof(kvr.kvr_attend_opts) == 5 * C.sizeof(C.c_void_p)
+
+
+def test_recent_size_follows_the_oracle_queue():
+    """kvr_recent_size against the oracle's Recent queue over a run of pushes."""
+    import numpy as np
+    for budget, slack in [(5, 0), (5, 3), (1, 7), (0, 2)]:
+        st = O.UnitState(64, 64, 1, 1, 128, O.hash_params_from_seed(1, 1), "f32", n_recent=budget, k_candidate=64)
+        r = 0
+        for t in range(30):
+            st.append(np.zeros(128), np.zeros(128))
+            st.compress(slack)                       # k_candidate is large: nothing reaches the sketch
+            r = kvr.kvr_recent_size(r + 1, budget, slack)
+            assert r == st.r_size
 
 
 def test_host_hash_matches_oracle():
@@ -139,12 +153,31 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     bad = list(ok_args); bad[15] = 65
     assert L.kvr_step_update(*bad) == kvr.KVR_ERR_UNSUPPORTED
     # attend
-    assert L.kvr_attend_decode(dp, None, p, p, p, 10, p, p, p, p, 20, p, p, 100, p, 1 << 30, None) == E
-    assert L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, None, 20, p, p, 100, p, 1 << 30, None) == E
-    assert L.kvr_attend_decode(dp, p, p, p, p, 10, None, None, p, p, 20, p, p, 100, p, 1 << 30, None) == E
-    assert L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, p, 20, p, p, 100, None, 0, None) == E
-    assert L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, p, 20, p, p, 100, p, 64, None) == kvr.KVR_ERR_WORKSPACE_TOO_SMALL
-    assert L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, p, 20, p, p, 0, p, 1 << 30, None) == E
+    assert L.kvr_attend_decode(dp, None, p, p, p, 10, p, p, p, p, 20, p, p, 100, p, 1 << 30, None, None) == E
+    assert L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, None, 20, p, p, 100, p, 1 << 30, None, None) == E
+    assert L.kvr_attend_decode(dp, p, p, p, p, 10, None, None, p, p, 20, p, p, 100, p, 1 << 30, None, None) == E
+    assert L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, p, 20, p, p, 100, None, 0, None, None) == E
+    assert L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, p, 20, p, p, 100, p, 64, None, None) == kvr.KVR_ERR_WORKSPACE_TOO_SMALL
+    assert L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, p, 20, p, p, 0, p, 1 << 30, None, None) == E
+    # attend options: a side stream comes with both of its events or not at all, the two timing
+    # events come as a pair, and the side stream is not the call's own stream
+    def attend_with(opts, stream=None):
+        return L.kvr_attend_decode(dp, p, p, p, p, 10, p, p, p, p, 20, p, p, 100, p, 64, C.byref(opts), stream)
+    h = 0x20000                                   # fake handles; never used: the workspace check fails first
+    assert attend_with(kvr.kvr_attend_opts(h, h, h, None, None)) == kvr.KVR_ERR_WORKSPACE_TOO_SMALL
+    assert attend_with(kvr.kvr_attend_opts(None, None, None, h, h)) == kvr.KVR_ERR_WORKSPACE_TOO_SMALL
+    assert attend_with(kvr.kvr_attend_opts(None, None, None, None, None)) == kvr.KVR_ERR_WORKSPACE_TOO_SMALL
+    assert attend_with(kvr.kvr_attend_opts(h, None, h, None, None)) == E
+    assert attend_with(kvr.kvr_attend_opts(h, h, None, None, None)) == E
+    assert attend_with(kvr.kvr_attend_opts(None, h, h, None, None)) == E
+    assert attend_with(kvr.kvr_attend_opts(None, None, None, h, None)) == E
+    assert attend_with(kvr.kvr_attend_opts(None, None, None, None, h)) == E
+    assert attend_with(kvr.kvr_attend_opts(h, h, h, None, None), stream=h) == E
+    # Recent queue size after a push (Algorithm 3, first branch)
+    assert L.kvr_recent_size(6, 5, 0) == 5 and L.kvr_recent_size(5, 5, 0) == 5 and L.kvr_recent_size(3, 5, 0) == 3
+    assert L.kvr_recent_size(8, 5, 3) == 8 and L.kvr_recent_size(9, 5, 3) == 5 and L.kvr_recent_size(40, 5, 3) == 5
+    assert L.kvr_recent_size(2 ** 31 - 1, 2 ** 31 - 1, 2 ** 31 - 1) == 2 ** 31 - 1
+    assert L.kvr_recent_size(-1, 5, 0) == E and L.kvr_recent_size(5, -1, 0) == E and L.kvr_recent_size(5, 5, -1) == E
     # hash helpers
     assert L.kvr_hash_params_from_seed(1, 0, None) == E
     assert L.kvr_hash_host(dp, -1, None, None) == E

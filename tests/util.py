@@ -55,14 +55,15 @@ def oracle_units_from_workload(wl: S.Workload, layer: int, units, *, acc_dtype=n
     return out
 
 
-def layer_state_from_oracle(kvr, LayerState, desc, states, B, Hkv, *, vague_cap, evict_cap=8):
+def layer_state_from_oracle(kvr, LayerState, desc, states, B, Hkv, *, vague_cap, evict_cap=8, slack=0, side=None):
     """Upload a list of oracle UnitStates (unit-major, B*Hkv of them) into a
     LayerState on the GPU."""
     s0 = states[0]
     ret_cap = len(s0.ret_pos)
     n_cap = len(s0.scores)
     ls = LayerState(desc, n_recent=s0.n_recent, k_candidate=s0.k_candidate, ret_cap=ret_cap,
-                    vague_cap=vague_cap, n_cap=n_cap, evict_cap=evict_cap)
+                    vague_cap=vague_cap, n_cap=n_cap, evict_cap=evict_cap, slack=slack, side=side)
+    ls.r_size = int(s0.r_size)
     dt = ls.dtype
     D = desc.head_dim
 
