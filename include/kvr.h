@@ -349,6 +349,30 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q,
                           void* ws, size_t ws_bytes, const kvr_attend_opts* opts, void* stream);
 
 /*
+ * kvr_attend_decode for callers that cannot allocate device memory or hand over a
+ * workspace: code running under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments (without ws / ws_bytes), same kernels and
+ * same results as kvr_attend_decode; the scratch memory is a fixed array of
+ * KVR_STATIC_SCRATCH_BYTES in device memory that belongs to the library's code
+ * object (each GPU the library runs on holds its own copy until the process
+ * ends).  The call allocates and frees nothing.  A call whose
+ * kvr_workspace_size(KVR_OP_ATTEND, ret_cap, vague_cap) exceeds
+ * KVR_STATIC_SCRATCH_BYTES is refused with KVR_ERR_WORKSPACE_TOO_SMALL before
+ * anything is launched (the named workloads need up to 70 MiB).  All calls on one
+ * GPU share that GPU's array: calls that can overlap in time (different streams,
+ * different host threads) race on it; order them on one stream or use
+ * kvr_attend_decode with separate workspaces.  Nothing in the array has to
+ * survive between calls and nothing in it needs clearing.
+ */
+#define KVR_STATIC_SCRATCH_BYTES (80u << 20)
+int32_t kvr_attend_decode_static(const kvr_desc* desc, const void* q,
+                                 const void* k_ret, const void* v_ret, const int32_t* ret_pos, int32_t ret_cap,
+                                 const void* sketch_k, const void* sketch_v,
+                                 const int32_t* vague_pos, const int32_t* n_vague, int32_t vague_cap,
+                                 float* out, float* scores, int64_t n_cap,
+                                 const kvr_attend_opts* opts, void* stream);
+
+/*
  * The Calculation Phase for n_q query tokens per sequence at once (a chunk of
  * prompt or of drafted tokens): as the Overview describes the phase, the layer's
  * cache is rebuilt once (Algorithm 4; Vague tokens by Algorithm 2: inside the

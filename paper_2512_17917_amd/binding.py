@@ -31,8 +31,9 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkvr.so")
 
 EXPORTS = ["kvr_version", "kvr_last_hip_error", "kvr_recent_size", "kvr_hash_params_from_seed", "kvr_hash_host",
            "kvr_workspace_size", "kvr_append", "kvr_select", "kvr_encode", "kvr_step_update",
-           "kvr_swap_back", "kvr_reconstruct", "kvr_attend_decode", "kvr_attend_multi_workspace_size",
-           "kvr_attend_multi"]
+           "kvr_swap_back", "kvr_reconstruct", "kvr_attend_decode", "kvr_attend_decode_static",
+           "kvr_attend_multi_workspace_size", "kvr_attend_multi"]
+KVR_STATIC_SCRATCH_BYTES = 80 << 20
 
 
 class KvrError(RuntimeError):
@@ -148,6 +149,9 @@ def lib() -> C.CDLL:
         L.kvr_attend_decode.restype = i32
         L.kvr_attend_decode.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, i64,
                                         vp, sz, C.POINTER(kvr_attend_opts), vp]
+        L.kvr_attend_decode_static.restype = i32
+        L.kvr_attend_decode_static.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, i64,
+                                               C.POINTER(kvr_attend_opts), vp]
         L.kvr_attend_multi_workspace_size.restype = i32
         L.kvr_attend_multi_workspace_size.argtypes = [dp, i32, i64, i64, C.POINTER(sz)]
         L.kvr_attend_multi.restype = i32
@@ -363,6 +367,23 @@ def kvr_attend_decode(desc, q, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_
         _ptr(scores, torch.float32, U * n_cap, "scores", True), n_cap, wp, wb,
         C.byref(opts) if opts is not None else None, _stream())
     _check("kvr_attend_decode", rc)
+
+
+def kvr_attend_decode_static(desc, q, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_v, vague_pos, n_vague,
+                             vague_cap, out, scores, n_cap, opts=None):
+    U, D, dt = desc.batch * desc.n_kv_heads, desc.head_dim, _torch_dtype(desc)
+    S = desc.r * desc.w * D
+    rc = lib().kvr_attend_decode_static(
+        C.byref(desc), _ptr(q, dt, desc.batch * desc.n_q_heads * D, "q"),
+        _ptr(k_ret, dt, U * ret_cap * D, "k_ret"), _ptr(v_ret, dt, U * ret_cap * D, "v_ret"),
+        _ptr(ret_pos, torch.int32, U * ret_cap, "ret_pos", True), ret_cap,
+        _ptr(sketch_k, dt, U * S, "sketch_k", True), _ptr(sketch_v, dt, U * S, "sketch_v", True),
+        _ptr(vague_pos, torch.int32, U * vague_cap, "vague_pos", True),
+        _ptr(n_vague, torch.int32, U, "n_vague", True), vague_cap,
+        _ptr(out, torch.float32, desc.batch * desc.n_q_heads * D, "out"),
+        _ptr(scores, torch.float32, U * n_cap, "scores", True), n_cap,
+        C.byref(opts) if opts is not None else None, _stream())
+    _check("kvr_attend_decode_static", rc)
 
 
 def kvr_attend_multi_workspace_size(desc, n_q, ret_cap, vague_cap) -> int:

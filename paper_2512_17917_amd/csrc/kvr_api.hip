@@ -50,6 +50,39 @@ int32_t finish(hipError_t e) {
 
 constexpr long long MAX_TOKENS = 1ll << 30;
 
+// ---------------------------------------------------------------------------
+// Workspace of kvr_attend_decode_static: a fixed array in device memory that is
+// part of the library's code object, so every GPU the library runs on holds its
+// own copy, at its own address, from the moment the code object is loaded there
+// until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address it yields for the current device is what
+// kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[KVR_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES];       // per device: address of its copy of `scratch`, null until looked up
+
+// Address of the current device's copy (looked up on the first call on that device).
+int32_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { g_last_hip_error = (int32_t)e; return KVR_ERR_HIP; }
+  if (dev < 0 || dev >= MAX_DEVICES) return KVR_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) {
+      g_last_hip_error = (int32_t)(e != hipSuccess ? e : hipErrorInvalidSymbol);
+      return KVR_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return KVR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -227,7 +260,7 @@ int32_t kvr_reconstruct(const kvr_desc* desc, const void* sketch_k, const void* 
                                         v_out, (hipStream_t)stream));
 }
 
-static int32_t attend_decode_common(const kvr_desc* desc, const void* q, const void* k_ret, const void* v_ret,
+static int32_t attend_decode_common(bool static_ws, const kvr_desc* desc, const void* q, const void* k_ret, const void* v_ret,
                           const int32_t* ret_pos, int32_t ret_cap, const void* sketch_k,
                           const void* sketch_v, const int32_t* vague_pos, const int32_t* n_vague,
                           int32_t vague_cap, float* out, float* scores, int64_t n_cap, void* ws,
@@ -258,6 +291,13 @@ static int32_t attend_decode_common(const kvr_desc* desc, const void* q, const v
       !aligned16(sketch_k) || !aligned16(sketch_v))
     return KVR_ERR_INVALID_ARG;
   const kvr::AttendPlan plan = kvr::attend_plan(d, desc->dtype, ret_cap, vague_cap);
+  if (static_ws) {
+    // the workspace is this device's copy of the library's static array
+    if (plan.total_bytes > (size_t)KVR_STATIC_SCRATCH_BYTES) return KVR_ERR_WORKSPACE_TOO_SMALL;
+    const int32_t rs = static_scratch(&ws);
+    if (rs != KVR_OK) return rs;
+    ws_bytes = (size_t)KVR_STATIC_SCRATCH_BYTES;
+  }
   if (ws == nullptr || !aligned16(ws)) return KVR_ERR_INVALID_ARG;
   if (ws_bytes < plan.total_bytes) return KVR_ERR_WORKSPACE_TOO_SMALL;
   kvr::AttendArgs a;
@@ -290,8 +330,17 @@ int32_t kvr_attend_decode(const kvr_desc* desc, const void* q, const void* k_ret
                           const void* sketch_v, const int32_t* vague_pos, const int32_t* n_vague,
                           int32_t vague_cap, float* out, float* scores, int64_t n_cap, void* ws,
                           size_t ws_bytes, const kvr_attend_opts* opts, void* stream) {
-  return attend_decode_common(desc, q, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_v, vague_pos, n_vague,
+  return attend_decode_common(false, desc, q, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_v, vague_pos, n_vague,
                               vague_cap, out, scores, n_cap, ws, ws_bytes, opts, stream);
+}
+
+int32_t kvr_attend_decode_static(const kvr_desc* desc, const void* q, const void* k_ret, const void* v_ret,
+                                 const int32_t* ret_pos, int32_t ret_cap, const void* sketch_k,
+                                 const void* sketch_v, const int32_t* vague_pos, const int32_t* n_vague,
+                                 int32_t vague_cap, float* out, float* scores, int64_t n_cap,
+                                 const kvr_attend_opts* opts, void* stream) {
+  return attend_decode_common(true, desc, q, k_ret, v_ret, ret_pos, ret_cap, sketch_k, sketch_v, vague_pos, n_vague,
+                              vague_cap, out, scores, n_cap, nullptr, 0, opts, stream);
 }
 
 static int32_t check_multi(const kvr_desc* desc, kvr::DevDesc& d, int32_t n_q) {

@@ -173,6 +173,13 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     assert attend_with(kvr.kvr_attend_opts(None, None, None, h, None)) == E
     assert attend_with(kvr.kvr_attend_opts(None, None, None, None, h)) == E
     assert attend_with(kvr.kvr_attend_opts(h, h, h, None, None), stream=h) == E
+    # the static-scratch entry point: same checks, and a call that needs more than the fixed array is refused
+    assert L.kvr_attend_decode_static(dp, None, p, p, p, 10, p, p, p, p, 20, p, p, 100, None, None) == E
+    assert L.kvr_attend_decode_static(dp, p, p, p, p, 10, p, p, p, p, 20, p, p, 0, None, None) == E
+    dbig = kvr.make_desc(64, 32, 8, 3, 273, kvr.KVR_BF16, seed=1)
+    assert kvr.kvr_workspace_size(dbig, kvr.KVR_OP_ATTEND, 7400, 25600) > kvr.KVR_STATIC_SCRATCH_BYTES
+    assert L.kvr_attend_decode_static(C.byref(dbig), p, p, p, p, 7400, p, p, p, p, 25600, p, p, 40000, None,
+                                      None) == kvr.KVR_ERR_WORKSPACE_TOO_SMALL
     # Recent queue size after a push (Algorithm 3, first branch)
     assert L.kvr_recent_size(6, 5, 0) == 5 and L.kvr_recent_size(5, 5, 0) == 5 and L.kvr_recent_size(3, 5, 0) == 3
     assert L.kvr_recent_size(8, 5, 3) == 8 and L.kvr_recent_size(9, 5, 3) == 5 and L.kvr_recent_size(40, 5, 3) == 5
