@@ -119,6 +119,7 @@ hipError_t launch_attend_vague_staged(const DevDesc& d, const AttendArgs& a, con
 hipError_t launch_attend_vague_staged64(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
                                         hipStream_t st);
 
+
 hipError_t launch_select(const DevDesc& d, const float* scores, long long n_cap, int32_t* ret_pos,
                          int ret_cap, const int32_t* n_ctx, int n_recent, int k_candidate,
                          int32_t* evict_slot, int32_t* evict_pos, int32_t* n_evict, int evict_cap,

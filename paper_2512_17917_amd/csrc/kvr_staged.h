@@ -54,6 +54,10 @@ __device__ __forceinline__ uint32_t pack_bf16_exact(float lo, float hi) {
   return (__float_as_uint(hi) & 0xffff0000u) | (__float_as_uint(lo) >> 16);
 }
 
+// (low half of a, low half of b) and (high half of a, high half of b) as one dword
+__device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pair_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
 // Packed minimum / maximum of two bf16 pairs on their raw bits (same argument as
 // for v_med3_f16: the order of finite values is the same in both formats).
 // Inline assembly again: results of these two may only feed ordinary vector-ALU
@@ -90,8 +94,12 @@ __device__ __forceinline__ uint32_t median_dword(const uint32_t (&x)[R], int mod
     const uint32_t m1 = pk_max_bits(pk_min_bits(x[0], x[1]), pk_min_bits(x[2], x[3]));
     const uint32_t m2 = pk_min_bits(pk_max_bits(x[0], x[1]), pk_max_bits(x[2], x[3]));
     if (mode == KVR_MEDIAN_LOWER) return pk_min_bits_last(m1, m2);
-    // their mean in float32, rounded once to bf16
-    return cvt_pk_bf16(0.5f * (bf_lo(m1) + bf_lo(m2)), 0.5f * (bf_hi(m1) + bf_hi(m2)));
+    // Their mean in float32, rounded once to bf16.  0.5 m1 + 0.5 m2 per channel is one v_dot2_f32_bf16 on
+    // the pair (m1, m2) against (0.5, 0.5): both products are exact, so the result is the float32 sum of two
+    // exactly known terms, the same value as 0.5f * (m1 + m2) formed with separate instructions (the halving
+    // only changes the exponent), in 5 instructions per dword instead of 9.
+    const uint32_t halves = 0x3f003f00u;
+    return cvt_pk_bf16(dot2_bf16(pair_lo(m1, m2), halves, 0.f), dot2_bf16(pair_hi(m1, m2), halves, 0.f));
   } else {
     float lo[R], hi[R];
 #pragma unroll
@@ -121,9 +129,6 @@ __device__ __forceinline__ uint4 xor4(uint4 v, uint32_t mask) {
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-// (low half of a, low half of b) and (high half of a, high half of b) as one dword
-__device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
-__device__ __forceinline__ uint32_t pair_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 __device__ __forceinline__ short4_t pack_k4(uint32_t k01, uint32_t k23) {
   return __builtin_bit_cast(short4_t, make_uint2(k01, k23));
 }
