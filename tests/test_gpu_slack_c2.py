@@ -229,3 +229,48 @@ def test_c2_all_units_follow_the_oracle(kvr, LayerState):
             worst_s = max(worst_s, np.abs(ls.scores[b, h].cpu().double().numpy() - st.scores.astype(np.float64)).max())
         say("c2 step", t, ": max |out - oracle| =", worst_o, "(max |out| =", big, ") max |score - oracle| =", worst_s)
         assert worst_o <= 2e-2 and worst_s <= 2e-5
+
+
+# ----------------------------------------------------------------------------- entirely on its own state
+@pytest.mark.parametrize("name,nsteps", [("c1", 32), ("tiny_bf16", 64)])
+def test_many_steps_entirely_on_the_gpus_own_state(kvr, LayerState, name, nsteps):
+    """After the prompt nothing is re-loaded from the oracle, not even the float scores: the library
+    runs nsteps decode steps on what it computed itself, the oracle runs beside it, and every step's
+    eviction, the whole integer state and the sketch must still agree bit for bit, outputs and scores
+    within tolerance.  (The other step tests re-load the scores so that one step's float rounding
+    cannot decide a later step's integer choice; on these seeded inputs it never does.)"""
+    if name == "c1":
+        wl = S.WORKLOADS["c1"]
+    else:
+        wl = S.small_workload(batch=2, n_q_heads=8, n_kv_heads=2, context=700, budget=0.25, r=3, steps=nsteps)
+    say("own state", name, nsteps, "steps")
+    layer = 0
+    units = [(b, h) for b in range(wl.batch) for h in range(wl.n_kv_heads)]
+    states = U.oracle_units_from_workload(wl, layer, units, extra_tokens=nsteps + 2)
+    params = states[0].params
+    d = kvr.make_desc(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.r, wl.w, wl.torch_dtype, hash_params=params)
+    G, scale = wl.group, d.softmax_scale
+    ls = U.layer_state_from_oracle(kvr, LayerState, d, states, wl.batch, wl.n_kv_heads,
+                                   vague_cap=wl.n_vague0 + nsteps + 2)
+    worst_o = worst_s = 0.0
+    for t in range(nsteps):
+        kn, vn = S.new_tokens(wl, layer, t)
+        q = S.queries(wl, layer, t + 1)
+        out = ls.decode_step(kn.cuda(), vn.cuda(), q.cuda(), check=True)
+        torch.cuda.synchronize()
+        og = out.cpu().double().numpy()
+        for u, (b, h) in enumerate(units):
+            st = states[u]
+            o_ref, (ws_, wp_), _ = st.decode_step(U.to_np(kn[b, h]), U.to_np(vn[b, h]), U.to_np(q[b, h * G:(h + 1) * G]),
+                                                  scale)
+            assert int(ls.n_evict[b, h]) == 1 and int(ls.evict_pos[b, h, 0]) == int(wp_[0]), (t, u)
+            if t % 8 == 7 or t == nsteps - 1:
+                compare_unit_state(ls, b, h, st, ("own state", t, u))
+            err = np.abs(og[b, h * G:(h + 1) * G] - o_ref).max()
+            if wl.torch_dtype == torch.float32:
+                err = err / max(np.abs(o_ref).max(), 1e-30)
+            worst_o = max(worst_o, err)
+            worst_s = max(worst_s, np.abs(ls.scores[b, h].cpu().double().numpy() - st.scores.astype(np.float64)).max())
+    say("own state", name, ": max out error", worst_o, "max score error", worst_s)
+    assert worst_o <= (1e-5 if wl.torch_dtype == torch.float32 else 2e-2)
+    assert worst_s <= 2e-5
