@@ -258,7 +258,7 @@ int32_t kvr_encode(const kvr_desc* desc, const void* k_src, const void* v_src, i
  * (also for n_recent = 0, where the token just appended is itself a Candidate)
  * and the same bit-reproducible sketch as the three separate calls.  Any number
  * of tokens up to evict_cap may leave a unit in one call (Slack > 0: see
- * kvr_recent_size).  For the decode steady state only: ret_cap <= 8192 and
+ * kvr_recent_size).  For the decode steady state only: ret_cap <= 32768 and
  * evict_cap <= 64, otherwise KVR_ERR_UNSUPPORTED (compress a prompt with the
  * separate calls).
  */

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libkvr.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["kvr_api.hip", "kvr_reconstruct.hip", "kvr_attend.hip", "kvr_attend_staged.hip", "kvr_attend_staged64.hip", "kvr_attend_retained.hip", "kvr_select.hip",
+SOURCES = ["kvr_api.hip", "kvr_reconstruct.hip", "kvr_attend.hip", "kvr_attend_staged.hip", "kvr_attend_staged64.hip", "kvr_attend_staged_r4.hip", "kvr_attend_retained.hip", "kvr_select.hip",
            "kvr_encode.hip", "kvr_swap.hip", "kvr_attend_multi.hip", "kvr_attend_multi_staged.hip"]
 
 # packed-FP32 instruction selection is switched off on purpose (ordinary float

@@ -217,7 +217,7 @@ int32_t kvr_step_update(const kvr_desc* desc, const void* k_new, const void* v_n
   if (n_cap < 1 || n_cap > MAX_TOKENS || ret_cap < 1 || n_recent < 0 || k_candidate < 0 || evict_cap < 1)
     return KVR_ERR_INVALID_ARG;
   if (vague_pos != nullptr && vague_cap < 1) return KVR_ERR_INVALID_ARG;
-  if (ret_cap > 8192 || evict_cap > 64) return KVR_ERR_UNSUPPORTED;
+  if (ret_cap > 32768 || evict_cap > 64) return KVR_ERR_UNSUPPORTED;
   return finish(kvr::launch_step_update(d, desc->dtype, k_new, v_new, n_ctx, k_ret, v_ret, ret_pos, ret_cap,
                                         scores, n_cap, n_recent, k_candidate, evict_slot, evict_pos, n_evict,
                                         evict_cap, vague_pos, n_vague, vague_cap, sketch_k, sketch_v,

@@ -505,9 +505,9 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
       // From here on the side stream may hold work that writes the caller's workspace: whatever
       // fails below, `st` is made to wait for it before this call returns.
       // what the staged kernel's two waves leave of a SIMD's 512 registers: 128 next to the 64-channel
-      // kernel, 80 next to the widest general form
+      // kernel, all it likes next to the four-row kernel (2 x 160 at most), 80 next to the widest general form
       const bool s64 = d.r == 3 && plan.ch == 64 && 3 * d.w <= 1024;
-      const int reg_form = s64 ? 1 : ((d.G == 4 && plan.ch <= 16) ? 2 : 0);
+      const int reg_form = s64 ? 1 : (staged_r4_applies(d) ? 0 : ((d.G == 4 && plan.ch <= 16) ? 2 : 0));
       e = launch_attend_retained(d, a, plan.n_rslices, cus, reg_form, sd.stream);
       const hipError_t ej = hipEventRecord(sd.join, sd.stream);
       if (e == hipSuccess && ej == hipSuccess) e = launch_attend_vague_staged(d, a, plan, st);

@@ -431,6 +431,7 @@ static hipError_t launch_r(const DevDesc& d, const AttendArgs& a, const AttendPl
 hipError_t launch_attend_vague_staged(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
                                       hipStream_t st) {
   if (d.r == 3 && plan.ch == 64 && 3 * d.w <= 1024) return launch_attend_vague_staged64(d, a, plan, st);
+  if (staged_r4_applies(d)) return launch_attend_vague_staged_r4(d, a, plan, st);
   switch (d.G) {
     case 1: return launch_r<1>(d, a, plan, st);
     case 2: return launch_r<2>(d, a, plan, st);

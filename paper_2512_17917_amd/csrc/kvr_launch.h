@@ -115,6 +115,10 @@ hipError_t launch_attend_multi(const DevDesc& d, const AttendArgs& a, const int3
 // Staged kernel over the Vague list (bf16, values signed only, G <= 4, r in {3,4}).
 hipError_t launch_attend_vague_staged(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
                                       hipStream_t st);
+// Its specialisation for r = 4 (kvr_attend_staged_r4.hip; launch_attend_vague_staged forwards to it).
+bool staged_r4_applies(const DevDesc& d);
+hipError_t launch_attend_vague_staged_r4(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
+                                         hipStream_t st);
 // Its specialisation for r = 3 and plan.ch = 64 (launch_attend_vague_staged forwards to it).
 hipError_t launch_attend_vague_staged64(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
                                         hipStream_t st);
@@ -129,7 +133,7 @@ hipError_t launch_append(const DevDesc& d, int dtype, const void* k_new, const v
                          const int32_t* n_ctx, void* k_ret, void* v_ret, int32_t* ret_pos, int ret_cap,
                          int32_t* out_slot, hipStream_t st);
 
-// append -> select -> encode of every unit in one launch (ret_cap <= 8192, evict_cap <= 64)
+// append -> select -> encode of every unit in one launch (ret_cap <= 32768, evict_cap <= 64)
 hipError_t launch_step_update(const DevDesc& d, int dtype, const void* k_new, const void* v_new,
                               const int32_t* n_ctx, void* k_ret, void* v_ret, int32_t* ret_pos, int ret_cap,
                               const float* scores, long long n_cap, int n_recent, int k_candidate,

@@ -120,7 +120,7 @@ class LayerState:
         # Algorithm 3, first branch: does the Recent queue hand its overhang on to the Candidates?
         self.r_size = kvr.kvr_recent_size(self.r_size + 1, self.n_recent, self.slack)
         if fused is None:
-            fused = self.ret_cap <= 8192 and self.evict_cap <= 64
+            fused = self.ret_cap <= 32768 and self.evict_cap <= 64
         if fused:
             self.step_update(k_new, v_new)
         else:

@@ -148,7 +148,7 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     assert L.kvr_step_update(*bad) == E
     bad = list(ok_args); bad[16] = None          # vague_pos without n_vague
     assert L.kvr_step_update(*bad) == E
-    bad = list(ok_args); bad[7] = 9000           # more slots than the fused kernel takes
+    bad = list(ok_args); bad[7] = 40000          # more slots than the fused kernel takes
     assert L.kvr_step_update(*bad) == kvr.KVR_ERR_UNSUPPORTED
     bad = list(ok_args); bad[15] = 65
     assert L.kvr_step_update(*bad) == kvr.KVR_ERR_UNSUPPORTED
