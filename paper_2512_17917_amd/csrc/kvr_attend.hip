@@ -56,16 +56,21 @@ AttendPlan attend_plan(const DevDesc& d, int dtype, long long ret_cap, long long
     if (ch) {
       const long long wr = (vague_cap + 63) / 64;          // wave-rounds to cover the list
       // Cost model: a workgroup that gives every wave rho rounds of 64 tokens takes
-      // about (2.8 + rho) round times (fixed part: staging four sketch chunks,
-      // hashes, softmax, reductions), and the launch runs ceil(workgroups / 256)
+      // about (fixed + rho) round times (fixed part: staging the sketch chunks,
+      // hashes, softmax, reductions: 2.8 rounds' worth for four 64-channel chunks,
+      // 7.5 for the sixteen 16-channel chunks of the four-row kernel, whose waves may
+      // also take more rounds), and the launch runs ceil(workgroups / 256)
       // such workgroups one after another on each CU.
+      const bool r4 = staged_r4_applies(d);
+      const int kmax = r4 ? STAGED_R4_KMAX : STAGED_KMAX;
+      const double fixed_rounds = r4 ? 7.5 : 2.8;
       double best = 1e30;
       int best_rho = 1, best_n = 1;
-      for (int rho = 1; rho <= STAGED_KMAX; ++rho) {
+      for (int rho = 1; rho <= kmax; ++rho) {
         const long long n = (wr + 8 * rho - 1) / (8 * rho);
         const long long rho_eff = (wr + 8 * n - 1) / (8 * n);      // rounds the busiest wave really gets
         const long long waves_of_wgs = (units * n + 255) / 256;
-        const double cost = (double)waves_of_wgs * (2.8 + (double)rho_eff);
+        const double cost = (double)waves_of_wgs * (fixed_rounds + (double)rho_eff);
         if (cost < best - 1e-9) { best = cost; best_rho = rho; best_n = (int)n; }
       }
       (void)best_rho;

@@ -40,7 +40,7 @@ constexpr int R4_ROWB = 32;               // bytes per LDS row
 constexpr int R4_NHP = 4;                 // 8-byte half pieces per LDS row
 constexpr int R4_NCHUNK = D / R4_CH;      // chunks per tensor
 constexpr int R4_NROW = ST_WAVES * 4;     // 16-lane rows per workgroup
-constexpr int R4_KMAX = ST_KMAX;
+constexpr int R4_KMAX = STAGED_R4_KMAX;   // wave-rounds (64 tokens) per wave
 
 struct Rows4 {
   uint2 r0, r1, r2, r3;
@@ -255,9 +255,16 @@ __device__ __forceinline__ void v_pass(const unsigned char* s_sk, const uint2 (&
     case 4: { constexpr int NK = 4; CALL; } break; \
     case 5: { constexpr int NK = 5; CALL; } break; \
     case 6: { constexpr int NK = 6; CALL; } break; \
+    case 7: { constexpr int NK = 7; CALL; } break; \
+    case 8: { constexpr int NK = 8; CALL; } break; \
+    case 9: { constexpr int NK = 9; CALL; } break; \
+    case 10: { constexpr int NK = 10; CALL; } break; \
+    case 11: { constexpr int NK = 11; CALL; } break; \
+    case 12: { constexpr int NK = 12; CALL; } break; \
+    case 13: { constexpr int NK = 13; CALL; } break; \
     default: break;              \
   }
-static_assert(ST_KMAX == 6, "KVR_DISPATCH_NK covers 1..6 rounds");
+static_assert(STAGED_R4_KMAX <= 13, "KVR_DISPATCH_NK covers 1..13 rounds");
 
 // LDS of a workgroup: one chunk, two sets of V partial sums [NROW][G][CH], wave statistics, q
 __host__ __device__ constexpr int chunk_bytes(int w) { return (4 * w * R4_ROWB + 1023) & ~1023; }
@@ -265,6 +272,8 @@ __host__ __device__ constexpr int stat_floats(int G) { return 3 * ST_WAVES * G; 
 __host__ __device__ constexpr size_t lds_need(int w, int G) {
   return (size_t)chunk_bytes(w) + (size_t)2 * R4_NROW * G * R4_CH * 4 + (size_t)stat_floats(G) * 4 + (size_t)G * 256;
 }
+
+}  // namespace
 
 template <int G, int MODE>
 __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_r4_kernel(DevDesc d, AttendArgs a) {
@@ -368,7 +377,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_r4_kernel(DevD
   float mx = -__builtin_inff();
 #pragma unroll
   for (int k = 0; k < KMAX; ++k) {
-    if (k >= n_k) break;                   // uniform over the wave: rounds it does not have cost nothing
+    if (k >= n_k) continue;                // uniform over the wave: rounds it does not have cost nothing
     const int tok0 = (gw_l + k * NWT) * 64 + (lane & ~3);        // first token of the quad in this round
     const int n_ok = nv - tok0;                                   // tokens i < n_ok of the quad exist
     float* lg = a.logits + ((size_t)unit_l * tot_cap + a.ret_cap + tok0) * G + sub;
@@ -394,7 +403,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_r4_kernel(DevD
     float lsum = 0.f;
 #pragma unroll
     for (int k = 0; k < KMAX; ++k) {
-      if (k >= n_k) break;
+      if (k >= n_k) continue;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float p = (s[k][i] == -__builtin_inff()) ? 0.f : __expf(s[k][i] - x);
@@ -515,7 +524,7 @@ __global__ __launch_bounds__(ST_THREADS) void attend_vague_staged_r4_kernel(DevD
 }
 
 template <int G, int MODE>
-hipError_t launch_r4(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
+static hipError_t launch_r4(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
   auto kern = attend_vague_staged_r4_kernel<G, MODE>;
   static std::once_flag once;
   static hipError_t attr_rc = hipSuccess;
@@ -531,12 +540,10 @@ hipError_t launch_r4(const DevDesc& d, const AttendArgs& a, const AttendPlan& pl
 }
 
 template <int G>
-hipError_t launch_r4_mode(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
+static hipError_t launch_r4_mode(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan, hipStream_t st) {
   return d.median_mode == KVR_MEDIAN_LOWER ? launch_r4<G, KVR_MEDIAN_LOWER>(d, a, plan, st)
                                            : launch_r4<G, KVR_MEDIAN_MIDMEAN>(d, a, plan, st);
 }
-
-}  // namespace
 
 bool staged_r4_applies(const DevDesc& d) {
   return d.r == 4 && 4 * d.w <= 4096 && d.G <= 4 && d.sign_mask == 2 && lds_need(d.w, d.G) <= (size_t)160 * 1024;

@@ -115,7 +115,10 @@ hipError_t launch_attend_multi(const DevDesc& d, const AttendArgs& a, const int3
 // Staged kernel over the Vague list (bf16, values signed only, G <= 4, r in {3,4}).
 hipError_t launch_attend_vague_staged(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
                                       hipStream_t st);
-// Its specialisation for r = 4 (kvr_attend_staged_r4.hip; launch_attend_vague_staged forwards to it).
+// Its specialisation for r = 4 (kvr_attend_staged_r4.hip; launch_attend_vague_staged forwards to it).  A wave
+// of that kernel takes up to STAGED_R4_KMAX rounds of 64 tokens (every workgroup stages the unit's whole
+// sketch, sixteen chunks of it, so few large workgroups are better than many small ones).
+constexpr int STAGED_R4_KMAX = 13;
 bool staged_r4_applies(const DevDesc& d);
 hipError_t launch_attend_vague_staged_r4(const DevDesc& d, const AttendArgs& a, const AttendPlan& plan,
                                          hipStream_t st);
