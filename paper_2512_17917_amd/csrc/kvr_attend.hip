@@ -502,7 +502,10 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
   // off with a launch as wide as its item count than with one workgroup per CU.
   const int cus = cu_count();
   const bool big = (long long)units * plan.n_vslices >= 2ll * cus;
-  const bool side = sd.stream != nullptr && plan.mfma_retained && plan.staged && big;
+  // Not next to the four-row kernel either: its two waves per SIMD hold up to 2 x 238 of the 512
+  // registers, so the retained kernel would only find room where a workgroup of it has just ended
+  // (measured on the 131k workload: 571 us side by side, 511 us back to back).
+  const bool side = sd.stream != nullptr && plan.mfma_retained && plan.staged && big && !staged_r4_applies(d);
   if (side) {
     e = hipEventRecord(sd.fork, st);
     if (e == hipSuccess) e = hipStreamWaitEvent(sd.stream, sd.fork, 0);
@@ -510,9 +513,9 @@ static hipError_t launch_g(const DevDesc& d, int dtype, const AttendArgs& a0, co
       // From here on the side stream may hold work that writes the caller's workspace: whatever
       // fails below, `st` is made to wait for it before this call returns.
       // what the staged kernel's two waves leave of a SIMD's 512 registers: 128 next to the 64-channel
-      // kernel, all it likes next to the four-row kernel (2 x 160 at most), 80 next to the widest general form
+      // kernel, 80 next to the widest general form
       const bool s64 = d.r == 3 && plan.ch == 64 && 3 * d.w <= 1024;
-      const int reg_form = s64 ? 1 : (staged_r4_applies(d) ? 0 : ((d.G == 4 && plan.ch <= 16) ? 2 : 0));
+      const int reg_form = s64 ? 1 : ((d.G == 4 && plan.ch <= 16) ? 2 : 0);
       e = launch_attend_retained(d, a, plan.n_rslices, cus, reg_form, sd.stream);
       const hipError_t ej = hipEventRecord(sd.join, sd.stream);
       if (e == hipSuccess && ej == hipSuccess) e = launch_attend_vague_staged(d, a, plan, st);
