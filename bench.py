@@ -31,18 +31,24 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 
 # Off-line counter readings (rocprofv3 --pmc, one run per counter group; the files give the commands), per
-# workload: they cannot be collected inside this program.  `traffic`: HBM bytes per kvr_attend_decode call
-# from FETCH_SIZE / WRITE_SIZE, each scaled by what the same counter reads for a copy kernel of known size
-# and the same access width (None: not measured for this workload).  `alu`: the staged kernel that rebuilds
+# workload: they cannot be collected inside this program.  `traffic`: bytes per kvr_attend_decode call at the
+# memory side of the L2, checked against a copy kernel of known size and against kernels of this library whose
+# traffic is known exactly (None: not measured for this workload).  `alu`: the staged kernel that rebuilds
 # the Vague tokens, which is bound by vector-ALU issue and LDS, not by HBM.
 OFFLINE_COUNTERS = {
     "c4": {
-        "traffic": None,
-        "traffic_note": "not reported: the FETCH_SIZE reading on hand is below the bytes the retained rows alone "
-                        "account for, so it is not a usable measurement (profiles/attend_pair_c4_hbm_traffic.txt)",
+        # bytes per kvr_attend_decode call at the memory side of the L2: read requests priced by their size
+        # (32 / 64 / 128 B request counters) + WRITE_SIZE, summed over the call's three kernels
+        "traffic": 781.5e6,
+        "traffic_note": "off-line counter reading (profiles/attend_call_c4_hbm_traffic.txt): 680.6 MB read "
+                        "(TCC_EA0_RDREQ by request size; FETCH_SIZE prices this chip's 128-byte requests at 64 "
+                        "bytes and reads half of that) + 100.9 MB written (WRITE_SIZE), retained + staged + merge "
+                        "kernel of one call; the 198 MB above the algorithmic bytes are the logits handed from the "
+                        "attention kernels to the score pass, the slice partials and whole lines pulled by "
+                        "4-byte score accesses",
         "alu": {"file": "profiles/attend_kernels_c4_sq_counters.txt", "kernel": "attend_vague_staged64_kernel<4>",
-                "valu_insts_per_launch": 60055680.0, "waves_per_launch": 10240,
-                "valu_busy": 0.72, "lds_busy": 0.42, "lds_bank_conflict_share": 0.46},
+                "valu_insts_per_launch": 60048000.0, "waves_per_launch": 10240,
+                "valu_busy": 0.71, "lds_busy": 0.41, "lds_bank_conflict_share": 0.46},
     },
 }
 # plain vector ALU peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second (the 157.3 TFLOP/s
@@ -161,7 +167,7 @@ def main():
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=8)
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run three elementwise kernels that read and write 1 GiB each (reference for "
+                    help="also run three elementwise kernels that read and write 768 MiB each (reference for "
                          "scaling the profiler's byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -405,10 +411,12 @@ def main():
         f"main kernel {avg_kern_s * 1e6:.1f} us/launch -> {achieved:.0f} GB/s")
 
     if args.calibrate_copy:
-        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        # an elementwise kernel of known traffic: reads 768 MiB, writes 768 MiB (a size nothing else in this
+        # program has, so that its dispatches can be told apart by grid size: 50 331 648 work-items)
+        src = torch.empty(3 << 26, dtype=torch.float32, device=dev)      # no fill kernel of the same size
         dst = torch.empty_like(src)
         for _ in range(3):
-            torch.add(src, 1.0, out=dst)        # an elementwise kernel: reads 1 GiB, writes 1 GiB
+            torch.add(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
 

@@ -207,8 +207,16 @@ __global__ __launch_bounds__(256) void encode_accum_kernel(
     const int32_t* __restrict__ ws_order, const int32_t* __restrict__ ws_start, T* __restrict__ sk,
     T* __restrict__ sv) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int s = blockIdx.x * 4 + wave;
-  const int row = blockIdx.y, unit = blockIdx.z;
+  // Workgroup ids are dealt round-robin to the 8 XCDs: all workgroups of a unit get ids that are equal
+  // modulo 8, and within a unit the sketch rows alternate fastest, so that the r owners of a token's
+  // slots, which walk the unit's list in the same ascending order at about the same time, share one L2.
+  const int per_unit = d.r * ((d.w + 3) >> 2);
+  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+  const int unit = (jj / per_unit) * 8 + xcd;
+  if (unit >= d.B * d.Hkv) return;
+  const int within = jj % per_unit;
+  const int row = within % d.r;
+  const int s = (within / d.r) * 4 + wave;
   if (s >= d.w) return;
   const size_t ur = (size_t)unit * d.r + row;
   const int lo = ws_start[ur * (d.w + 1) + s], hi = ws_start[ur * (d.w + 1) + s + 1];
@@ -287,7 +295,7 @@ static hipError_t launch_t(const DevDesc& d, const void* k_src, const void* v_sr
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(encode_accum_kernel<T>, dim3((d.w + 3) / 4, d.r, units), dim3(256), 0, st, d,
+  hipLaunchKernelGGL(encode_accum_kernel<T>, dim3((unsigned)(((units + 7) / 8) * 8 * d.r * ((d.w + 3) / 4))), dim3(256), 0, st, d,
                      (const T*)k_src, (const T*)v_src, src_rows, cap, ws_order, ws_start, (T*)sk, (T*)sv);
   return hipGetLastError();
 }
