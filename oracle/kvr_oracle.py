@@ -237,8 +237,9 @@ def swap_pick(scores, ret_pos, vague_pos, n_ctx: int, n_recent: int, replace_rat
 
 def swap_once(SK, SV, params, K_ret, V_ret, ret_pos, vague_pos, s_min: int, i_max: int, *,
               storage="f64", acc_dtype=np.float64, median_mode="midmean", sign_mask=2):
-    """The body of the swap loop for the chosen pair:
-        tmp <- V.Query(J);  V.Delete(tmp);  V.Insert(C.Top_Pop());  C.Push(tmp)
+    """The body of the swap loop for the chosen pair (Algorithm 3, second loop):
+    query the Vague token J, delete that estimate from the sketch, insert the
+    popped Candidate, push the estimate into the Candidate part.
     J = vague_pos[i_max]; the popped Candidate sits in retained slot s_min.
     V.Delete subtracts the queried estimate tmp from exactly the slots that an
     insert of J adds to (with the same signs); Delete and Insert form one sketch
@@ -388,14 +389,13 @@ class UnitState:
         return slot
 
     def compress(self, slack=0):
-        """Algorithm 3 without the swap loop, after R.Push.  The Recent part is a
-        queue over the r_size newest positions; n_recent is R.budget.
-            if R.size > R.budget + Slack:  C.Push(R.Pop_k(R.size - R.budget))
-        i.e. only when the queue has outgrown its budget by more than `slack` do its
-        oldest R.size - R.budget tokens leave it, all at once; then
-            while C.size > C.budget:  V.Insert(C.Top_Pop())
-        moves the lowest-score Candidates into the sketch (one insert call in
-        ascending slot order: a slot shared by several of them is rounded once).
+        """Algorithm 3 without the swap loop, after the push of the new token.  The
+        Recent part is a queue over the r_size newest positions; n_recent is its
+        budget.  First branch: only when the queue has outgrown its budget by more
+        than `slack` do its oldest (size - budget) tokens leave it for the Candidate
+        part, all at once.  Then, as long as the Candidate part is over its budget,
+        its lowest-score token moves into the sketch (one insert call in ascending
+        slot order: a slot shared by several of them is rounded once).
         slack = 0: one token in, one token out per step."""
         if self.r_size > self.n_recent + slack:
             self.r_size = self.n_recent
