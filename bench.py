@@ -136,7 +136,7 @@ def cpu_baseline(wl, n_units):
     }
 
 
-def main():
+def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
@@ -169,12 +169,20 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three elementwise kernels that read and write 768 MiB each (reference for "
                          "scaling the profiler's byte counters)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the other named workloads (c3, c5, c2) that a default run "
+                         "reports beside the headline figure")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+    return args
 
+
+def run_workload(args):
+    """Builds the compressed state of every layer of args.workload, times the decode steps and returns the
+    result object (without the CPU baseline).  Everything it allocates on the GPU is released on return."""
     import torch
     import kvr_synth as S
     from paper_2512_17917_amd import binding as kvr
@@ -420,13 +428,43 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    return result
+
+
+# the other named workloads, measured briefly in a default run so that their figures come from the same
+# program on the same machine as the headline: (name, timed steps, warm-up steps)
+OTHER_WORKLOADS = (("c3", 32, 4), ("c5", 12, 2), ("c2", 128, 4))
+
+
+def main():
+    args = parse_args()
+    import torch
+    import kvr_synth as S
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    result = run_workload(args)
+    torch.cuda.empty_cache()
+    headline = (args.workload == "c4" and args.layers is None and args.replace_rate is None
+                and args.layer_budget_ramp == 0.0 and args.slack == 0 and args.multi_q == 0
+                and not args.calibrate_copy)
+    if headline and not args.no_other_workloads:
+        others = {}
+        for name, k, w_ in OTHER_WORKLOADS:
+            a2 = argparse.Namespace(**vars(args))
+            a2.workload, a2.steps, a2.warmup = name, k, w_
+            r = run_workload(a2)
+            torch.cuda.empty_cache()
+            others[name] = {"value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"],
+                            "steps": k, "warmup": w_, "workload": r["config"]["workload"],
+                            "hbm_frac_whole_step": r["hbm_frac_whole_step"],
+                            "attend_call_us": r["roofline"]["avg_launch_ms"] * 1e3,
+                            "attend_call_hbm_frac": r["roofline"]["frac"],
+                            "prompt_compress_ms_per_layer": r["prompt_compress"]["ms_per_layer"]}
+        result["other_workloads"] = others
     if args.skip_cpu_baseline:
         result["cpu_baseline"] = None
     else:
-        del layers, knew, vnew, qs
-        torch.cuda.empty_cache()
         torch.set_num_threads(1)
-        result["cpu_baseline"] = cpu_baseline(wl, args.cpu_units)
+        result["cpu_baseline"] = cpu_baseline(S.WORKLOADS[args.workload], args.cpu_units)
         log(f"[bench] oracle: {result['cpu_baseline']['value']:.3e} steps/s ({result['cpu_baseline']['sample']})")
     print(json.dumps(result), flush=True)
 
