@@ -285,9 +285,11 @@ def test_append(kvr, dtype):
 
 # ----------------------------------------------------------------------------- attend
 def run_attend_case(kvr, rng, dtype, B, Hq, Hkv, r, w, ret_cap, n_vagues, vague_cap, mask=2, mode=0,
-                    free_frac=0.1, with_scores=True, identity=False, kscale=1.0, side=None, keep=None):
+                    free_frac=0.1, with_scores=True, identity=False, kscale=1.0, side=None, keep=None,
+                    check_units=None):
     """side: a binding.SideStream lent to the call (None: the kernels run back to back).
-    keep: a list that receives (out, scores) of the call as CPU tensors."""
+    keep: a list that receives (out, scores) of the call as CPU tensors.
+    check_units: the (b, h) units the oracle is run for (None: all of them)."""
     D = 128
     G = Hq // Hkv
     d = kvr.make_desc(B, Hq, Hkv, r, w, dtype, seed=77, sign_mask=mask, median_mode=mode)
@@ -326,8 +328,11 @@ def run_attend_case(kvr, rng, dtype, B, Hq, Hkv, r, w, ret_cap, n_vagues, vague_
     if keep is not None:
         keep.append((out.cpu().clone(), sc.cpu().clone() if sc is not None else None))
     worst = 0.0
+    assert np.isfinite(og).all()
     for b in range(B):
         for h in range(Hkv):
+            if check_units is not None and (b, h) not in check_units:
+                continue
             n = min(max(int(nv[b, h]), 0), vague_cap)
             vp = vague_pos[b, h, :n].tolist()
             used = ret_pos[b, h] >= 0
@@ -412,6 +417,20 @@ def test_attend_staged_channel_chunks(kvr):
         run_attend_case(kvr, rng, dtype, 1, 2 * G, 2, r, w, 130, nv, cap, mode=mode)
     say("attend staged, many units (XCD mapping), 3 rounds per wave")
     run_attend_case(kvr, rng, dtype, 3, 12, 3, 3, 50, 70, [4000, 3999, 1, 0, 64, 65, 2500, 4100, 128], 4100)
+
+
+@pytest.mark.parametrize("G,mode", [(1, 0), (2, 1), (4, 0)])
+def test_attend_four_rows_many_rounds(kvr, G, mode):
+    """Four sketch rows with so many units that the plan gives every unit one workgroup: a wave of the
+    four-row staged kernel then takes up to 13 rounds of 64 tokens.  Units with shorter lists exercise the
+    round counts in between, a ragged last round, one token and none.  Both median rules."""
+    B, Hkv, cap = 32, 8, 6656
+    lens = {(0, 0): 6656, (0, 1): 6593, (5, 3): 5000, (17, 6): 3300, (31, 7): 1, (31, 6): 0, (12, 0): 4161}
+    nv = [lens.get((u // Hkv, u % Hkv), 6656 - 64 * (u % 7)) for u in range(B * Hkv)]
+    rng = np.random.default_rng(61 + G)
+    say("attend four rows, up to 13 rounds per wave", G, mode)
+    run_attend_case(kvr, rng, torch.bfloat16, B, Hkv * G, Hkv, 4, 64, 70, nv, cap, mode=mode,
+                    check_units=set(lens))
 
 
 @pytest.mark.parametrize("G", [1, 2, 4])
