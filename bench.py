@@ -54,6 +54,8 @@ OFFLINE_COUNTERS = {
 # plain vector ALU peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second (the 157.3 TFLOP/s
 # fp32 vector figure / 2 flops per FMA / 2 for packed math, which this build switches off)
 ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# LDS peak: 256 CUs x 128 bytes per clock x 2.4 GHz
+LDS_PEAK_TBS = 256 * 128 * 2.4e9 / 1e12
 
 
 def algorithmic_bytes_per_unit(wl, n_ctx):
@@ -324,6 +326,12 @@ def run_workload(args):
             "lds_bank_conflict_share": c["lds_bank_conflict_share"],
             "valu_insts_per_wave": c["valu_insts_per_launch"] / c["waves_per_launch"],
             "valu_insts_per_rebuilt_token": c["valu_insts_per_launch"] * 64 / (wl.units_per_layer * n_vague_mid),
+            # what the rebuilt part must gather out of the on-chip sketch copy: r rows of K and of V per token
+            "lds_gather_bytes_per_launch": wl.units_per_layer * n_vague_mid * 2 * wl.r * D * e_bytes,
+            "lds_gather_tbs": wl.units_per_layer * n_vague_mid * 2 * wl.r * D * e_bytes / avg_kern_s / 1e12,
+            "lds_peak_tbs": LDS_PEAK_TBS,
+            "lds_frac": wl.units_per_layer * n_vague_mid * 2 * wl.r * D * e_bytes / avg_kern_s / 1e12 / LDS_PEAK_TBS,
+            "lds_peak_derivation": "256 CUs x 128 B per clock x 2.4 GHz",
             "note": "instruction counts and busy fractions are off-line counter readings of the kernel running "
                     "alone (the file gives the command); the duration is this run's",
         }
