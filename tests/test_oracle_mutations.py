@@ -154,6 +154,31 @@ def _swap_pick_no_rate(scores, ret_pos, vague_pos, n_ctx, n_recent, replace_rate
     return _swap_pick(scores, ret_pos, vague_pos, n_ctx, n_recent, 1.0)
 
 
+def _insert_delete_adds(SK, SV, params, tok_pos, K_tok, V_tok, **kw):
+    kw = dict(kw)
+    if kw.get("coef") is not None:
+        kw["coef"] = [abs(int(c)) for c in kw["coef"]]      # V.Delete adds instead of subtracting
+    return _insert(SK, SV, params, tok_pos, K_tok, V_tok, **kw)
+
+
+_revive = O.revive
+
+
+def _revive_rotated(K_ret, V_ret, ret_pos, SK, SV, params, vague_pos, n_ctx, **kw):
+    K, V = _revive(K_ret, V_ret, ret_pos, SK, SV, params, vague_pos, n_ctx, **kw)
+    vp = [int(p) for p in vague_pos]
+    if len(vp) > 1:                                  # every rebuilt token lands on the next Vague position
+        K[vp], V[vp] = K[vp[1:] + vp[:1]].copy(), V[vp[1:] + vp[:1]].copy()
+    return K, V
+
+
+_attend_multi = O.attend_multi
+
+
+def _attend_multi_sees_one_more(q, q_pos, *a, **kw):
+    return _attend_multi(q, [int(x) + 1 for x in q_pos], *a, **kw)
+
+
 HASH = [P.test_bucket_closed_forms, P.test_bucket_range_uniformity_and_sign_balance]
 INSERT = [P.test_insert_linearity_and_mass, P.test_insert_sign_mask_variants,
           P.test_insert_rounding_once_per_slot_in_list_order, P.test_whole_step_against_onehot_formulation]
@@ -164,6 +189,12 @@ SELECT = [P.test_select_against_lexsort_and_edges, P.test_multi_step_bookkeeping
 ATTEND = [P.test_attention_matches_library_sdpa, P.test_full_budget_equals_dense_attention_and_score_mass]
 SWAP = [P.test_swap_pick_against_brute_force_and_boundaries, P.test_swap_loop_exit_condition_and_partition]
 STORAGE = [P.test_to_storage_matches_torch_bf16]
+SWAP_BODY = [P.test_swap_restores_token_exactly_without_collisions, P.test_swap_with_collisions_against_onehot_formulation,
+             P.test_swap_rounds_shared_slot_once_delete_then_insert]
+REVIVE = [P.test_fused_equals_dense_over_reconstruction_and_permutation_invariance,
+          P.test_whole_step_against_onehot_formulation]
+MULTI = [P.test_attend_multi_against_library_sdpa_with_mask,
+         P.test_attend_multi_equals_one_query_at_a_time_on_the_truncated_context]
 
 MUTATIONS = [
     ("bucket from the low word", "bucket_of", _bucket_low_word, HASH),
@@ -184,12 +215,15 @@ MUTATIONS = [
     ("signs on the keys instead of the values", "insert", _insert_signs_on_keys, INSERT),
     ("query ignores the signs", "query", _query_ignores_signs, QUERY + INSERT),
     ("swap decision without ReplaceRate", "swap_pick", _swap_pick_no_rate, SWAP),
+    ("delete adds instead of subtracting", "insert", _insert_delete_adds, SWAP_BODY),
+    ("rebuilt tokens at the wrong positions", "revive", _revive_rotated, REVIVE),
+    ("a query sees one later position", "attend_multi", _attend_multi_sees_one_more, MULTI),
 ]
 
 
 def test_pins_pass_unmodified():
     """The reference point: with nothing planted every pin used below passes."""
-    for group in (HASH, INSERT, QUERY, SELECT, ATTEND, SWAP, STORAGE):
+    for group in (HASH, INSERT, QUERY, SELECT, ATTEND, SWAP, STORAGE, SWAP_BODY, REVIVE, MULTI):
         for pin in group:
             pin()
 
