@@ -394,46 +394,52 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(DevDesc d, AttendAr
   }
 
   // ---- the unit's output: spread over the first nb workgroups of the unit (a power
-  //      of two <= 8): workgroup bx takes G*D/nb output elements, four threads per
-  //      element, each summing every fourth slice with eight loads in flight; a
-  //      unit cut into many slices (few units, long lists) would otherwise spend
-  //      its time in one thread's walk over the slices. ------------------------------
+  //      of two): workgroup bx takes G*D/nb output elements, `tpe` threads per
+  //      element, each summing every tpe-th slice with eight loads in flight.  A
+  //      unit cut into many slices (few units, long lists) gets 16 threads per
+  //      element and up to 32 workgroups, so that a thread's walk over the slices
+  //      is one batch of loads; otherwise 4 threads and up to 8 workgroups. ----------
+  const int tpe = (a.n_slices > 32) ? 16 : 4;
+  const int epw = 256 / tpe;                  // output elements per workgroup and round
   int nb = 1;
-  while (nb * 2 <= 8 && nb * 2 <= (int)gridDim.x) nb *= 2;
+  while (nb * 2 <= 2 * tpe && nb * 2 <= (int)gridDim.x && G * D / (nb * 2) >= epw) nb *= 2;
   if ((int)blockIdx.x < nb) {
-    __shared__ float sO[4][64];                // [slice quarter][output element of this round]
-    const int per_wg = G * D / nb;            // 16 .. 1024, multiple of 16
+    __shared__ float sO[16][64];               // [slice share][output element of this round]
+    const int per_wg = G * D / nb;             // a multiple of epw
     const float* po = a.part_o + (size_t)unit * a.n_slices * G * D;
-    for (int o0 = 0; o0 < per_wg; o0 += 64) {
-      const int ol = o0 + (tid & 63), sq = tid >> 6;
-      const int idx = blockIdx.x * per_wg + ol;
-      const bool live = ol < per_wg;
-      const int g = live ? idx / D : 0;
+    for (int o0 = 0; o0 < per_wg; o0 += epw) {
+      const int el = tid % epw, sq = tid / epw;
+      const int idx = blockIdx.x * per_wg + o0 + el;
+      const int g = idx / D;
       const float M = sM[g];
       float o = 0.f;
-      if (live) {
-        for (int s0 = sq; s0 < a.n_slices; s0 += 4 * 8) {
-          float v[8], wgt[8];
+      for (int s0 = sq; s0 < a.n_slices; s0 += tpe * 8) {
+        float v[8], wgt[8];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const int s_ = s0 + 4 * j;
-            v[j] = 0.f;
-            wgt[j] = 0.f;
-            if (s_ < a.n_slices) {
-              v[j] = po[(size_t)s_ * G * D + idx];
-              const float ms = pml[(s_ * G + g) * 2], ls = pml[(s_ * G + g) * 2 + 1];
-              wgt[j] = (ls > 0.f) ? expf(ms - M) : 0.f;
-            }
+        for (int j = 0; j < 8; ++j) {
+          const int s_ = s0 + tpe * j;
+          v[j] = 0.f;
+          wgt[j] = 0.f;
+          if (s_ < a.n_slices) {
+            v[j] = po[(size_t)s_ * G * D + idx];
+            const float ms = pml[(s_ * G + g) * 2], ls = pml[(s_ * G + g) * 2 + 1];
+            wgt[j] = (ls > 0.f) ? expf(ms - M) : 0.f;
           }
-#pragma unroll
-          for (int j = 0; j < 8; ++j) o = fmaf(v[j], wgt[j], o);
         }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o = fmaf(v[j], wgt[j], o);
       }
       __syncthreads();                         // previous round's readers are done with sO
-      sO[sq][tid & 63] = o;
+      sO[sq][el] = o;
       __syncthreads();
-      if (sq == 0 && live) {
-        const float tot = (sO[0][tid] + sO[1][tid]) + (sO[2][tid] + sO[3][tid]);
+      if (sq == 0) {
+        float tot = 0.f;
+        if (tpe == 4) {
+          tot = (sO[0][el] + sO[1][el]) + (sO[2][el] + sO[3][el]);
+        } else {
+#pragma unroll
+          for (int k = 0; k < 16; k += 4) tot += (sO[k][el] + sO[k + 1][el]) + (sO[k + 2][el] + sO[k + 3][el]);
+        }
         const float L = sL[g];
         // column g of the partials = (query tq, head gh of the group); out is [B, n_q, Hq, D]
         const int tq = g / d.G, gh = g % d.G;
