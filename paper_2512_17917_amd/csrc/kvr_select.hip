@@ -131,12 +131,13 @@ __global__ __launch_bounds__(SEL_THREADS) void step_update_kernel(
         pre_sc[j] = (pos_new >= 0 && pos_new < n_cap) ? scores[(size_t)unit * n_cap + pos_new] : 0.f;
       }
   }
+  __shared__ EvictHandOver ho;
   __syncthreads();          // the new row and its ret_pos entry are visible to the whole workgroup
   select_body<true, KPT>(d, unit, scores, n_cap, ret_pos, ret_cap, n_ctx, n_recent, k_cand, evict_slot, evict_pos,
-                         n_evict, evict_cap, vague_pos, n_vague, vague_cap, pre, pre_sc);
-  __syncthreads();          // the eviction list and its count are visible
+                         n_evict, evict_cap, vague_pos, n_vague, vague_cap, pre, pre_sc, &ho);
+  __syncthreads();          // the eviction list and its count are visible (in LDS; global memory has them too)
   encode_small_body<T>(d, unit, k_ret, v_ret, ret_cap, evict_slot, evict_pos, n_evict, evict_cap, sk, sv,
-                       nullptr, nullptr);
+                       nullptr, nullptr, &ho);
 }
 
 hipError_t launch_step_update(const DevDesc& d, int dtype, const void* k_new, const void* v_new,

@@ -29,6 +29,14 @@ struct SelShared {
   int nlist, list[SEL_SMALL];        // small eviction counts: the evicted slots, in any order
 };
 
+// Eviction list of one unit in LDS: how the fused update kernel hands the selection's result to the
+// insert without a round trip through global memory (the lists in global memory are written as well).
+struct EvictHandOver {
+  int cnt;                           // 0 if nothing is evicted or the lists would overflow
+  int slot[ENC_SMALL_CAP];
+  int pos[ENC_SMALL_CAP];
+};
+
 // ---------------------------------------------------------------------------
 // append
 // ---------------------------------------------------------------------------
@@ -226,7 +234,7 @@ __device__ __forceinline__ void select_body(
     int32_t* __restrict__ ret_pos, int ret_cap, const int32_t* __restrict__ n_ctx, int n_recent, int k_cand,
     int32_t* __restrict__ evict_slot, int32_t* __restrict__ evict_pos, int32_t* __restrict__ n_evict,
     int evict_cap, int32_t* __restrict__ vague_pos, int32_t* __restrict__ n_vague, int vague_cap,
-    const int* pre = nullptr, const float* pre_sc = nullptr) {
+    const int* pre = nullptr, const float* pre_sc = nullptr, EvictHandOver* ho = nullptr) {
   const int b = unit / d.Hkv;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -273,12 +281,18 @@ __device__ __forceinline__ void select_body(
   __syncthreads();
   const int n_e = sh.cnt - k_cand;
   if (n_e <= 0) {
-    if (tid == 0) n_evict[unit] = 0;
+    if (tid == 0) {
+      n_evict[unit] = 0;
+      if (ho) ho->cnt = 0;
+    }
     return;
   }
   const int nv_old = (vague_pos && n_vague) ? clampi(n_vague[unit], 0, vague_cap) : 0;
   if (n_e > evict_cap || (vague_pos && n_vague && nv_old + n_e > vague_cap)) {
-    if (tid == 0) n_evict[unit] = -n_e;
+    if (tid == 0) {
+      n_evict[unit] = -n_e;
+      if (ho) ho->cnt = 0;
+    }
     return;
   }
 
@@ -336,6 +350,7 @@ __device__ __forceinline__ void select_body(
           const int pos = key_pos(rkey[j]);
           evict_slot[(size_t)unit * evict_cap + idx] = slot;
           evict_pos[(size_t)unit * evict_cap + idx] = pos;
+          if (ho && idx < ENC_SMALL_CAP) { ho->slot[idx] = slot; ho->pos[idx] = pos; }
           rp[slot] = -1;
           if (vague_pos && n_vague) vague_pos[(size_t)unit * vague_cap + nv_old + idx] = pos;
         }
@@ -343,6 +358,7 @@ __device__ __forceinline__ void select_body(
     }
     if (tid == 0) {
       n_evict[unit] = n_e;
+      if (ho) ho->cnt = n_e;
       if (vague_pos && n_vague) n_vague[unit] = nv_old + n_e;
     }
     return;
@@ -372,6 +388,7 @@ __device__ __forceinline__ void select_body(
       const int pos = key_pos(key);
       evict_slot[(size_t)unit * evict_cap + idx] = slot;
       evict_pos[(size_t)unit * evict_cap + idx] = pos;
+      if (ho && idx < ENC_SMALL_CAP) { ho->slot[idx] = slot; ho->pos[idx] = pos; }
       rp[slot] = -1;
       if (vague_pos && n_vague) vague_pos[(size_t)unit * vague_cap + nv_old + idx] = pos;
     }
@@ -381,6 +398,7 @@ __device__ __forceinline__ void select_body(
   }
   if (tid == 0) {
     n_evict[unit] = n_e;
+    if (ho) ho->cnt = n_e;
     if (vague_pos && n_vague) n_vague[unit] = nv_old + n_e;
   }
 }
@@ -396,15 +414,16 @@ __device__ __forceinline__ void encode_small_body(
     const DevDesc& d, int unit, const T* __restrict__ k_src, const T* __restrict__ v_src, int src_rows,
     const int32_t* __restrict__ src_slot, const int32_t* __restrict__ tok_pos,
     const int32_t* __restrict__ count, int cap, T* __restrict__ sk, T* __restrict__ sv,
-    int32_t* __restrict__ out_bucket, uint8_t* __restrict__ out_sign) {
+    int32_t* __restrict__ out_bucket, uint8_t* __restrict__ out_sign, const EvictHandOver* ho = nullptr) {
   __shared__ int s_bucket[ENC_SMALL_CAP][KVR_MAX_ROWS];
   __shared__ int s_slot[ENC_SMALL_CAP];
   __shared__ unsigned s_sign[ENC_SMALL_CAP];
   const int tid = threadIdx.x;
-  const int cnt = clampi(count[unit], 0, min(cap, ENC_SMALL_CAP));
+  // the list comes from LDS when the selection ran in this workgroup just before (fused update)
+  const int cnt = clampi(ho ? ho->cnt : count[unit], 0, min(cap, ENC_SMALL_CAP));
   if (tid < cnt) {
-    const int J = tok_pos[(size_t)unit * cap + tid];
-    const int slot = src_slot[(size_t)unit * cap + tid];
+    const int J = ho ? ho->pos[tid] : tok_pos[(size_t)unit * cap + tid];
+    const int slot = ho ? ho->slot[tid] : src_slot[(size_t)unit * cap + tid];
     s_slot[tid] = (slot >= 0 && slot < src_rows) ? slot : -1;
     unsigned sg = 0;
     for (int i = 0; i < d.r; ++i) {
