@@ -171,6 +171,9 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three elementwise kernels that read and write 768 MiB each (reference for "
                          "scaling the profiler's byte counters)")
+    ap.add_argument("--reconstruct", action="store_true",
+                    help="also time the stand-alone kvr_reconstruct (Algorithm 2 for every Vague token of a layer, "
+                         "rebuilt K and V written to memory) on every layer; reported beside the headline figure")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short runs of the other named workloads (c3, c5, c2) that a default run "
                          "reports beside the headline figure")
@@ -411,6 +414,33 @@ def run_workload(args):
                                   "decode_ms_per_layer_for_comparison": result["ms_per_step"] / L}
         log(f"[bench] attend_multi n_q={nq}: {ms_layer * 1e3:.1f} us per layer")
         del ws_m
+    if args.reconstruct:
+        ls0 = layers[0]
+        cap_r = ls0.vague_cap
+        k_out = torch.empty(B, Hkv, cap_r, D, dtype=wl.torch_dtype, device=dev)
+        v_out = torch.empty_like(k_out)
+        for l in range(min(L, 4)):
+            kvr.kvr_reconstruct(descs[l], layers[l].sketch_k, layers[l].sketch_v, layers[l].vague_pos,
+                                layers[l].n_vague, layers[l].vague_cap, k_out, v_out)
+        torch.cuda.synchronize()
+        reps = 3
+        tr0 = time.perf_counter()
+        for _ in range(reps):
+            for l in range(L):
+                kvr.kvr_reconstruct(descs[l], layers[l].sketch_k, layers[l].sketch_v, layers[l].vague_pos,
+                                    layers[l].n_vague, layers[l].vague_cap, k_out, v_out)
+        torch.cuda.synchronize()
+        ms_layer = (time.perf_counter() - tr0) * 1e3 / (reps * L)
+        n_v = int(ls0.n_vague.max().item())
+        # rebuilt K and V written once, the sketch and the index list read once
+        rbytes = wl.units_per_layer * (2 * n_v * D * e_bytes + 2 * wl.sketch_slots * D * e_bytes + 4 * n_v)
+        result["reconstruct"] = {"ms_per_layer": ms_layer, "tokens_per_layer": wl.units_per_layer * n_v,
+                                 "algorithmic_bytes_per_layer": rbytes,
+                                 "achieved_gbs": rbytes / (ms_layer * 1e-3) / 1e9,
+                                 "hbm_frac": rbytes / (ms_layer * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        log(f"[bench] kvr_reconstruct: {ms_layer * 1e3:.1f} us per layer, {result['reconstruct']['achieved_gbs']:.0f} GB/s "
+            f"({100 * result['reconstruct']['hbm_frac']:.1f}% of HBM peak)")
+        del k_out, v_out
     if args.replace_rate is not None:
         n_sw = torch.zeros(B, Hkv, dtype=torch.int32, device=dev)
         layers[0].swap_back(args.replace_rate, args.max_swaps, n_sw)       # one more loop, to report its count
@@ -453,7 +483,7 @@ def main():
     torch.cuda.empty_cache()
     headline = (args.workload == "c4" and args.layers is None and args.replace_rate is None
                 and args.layer_budget_ramp == 0.0 and args.slack == 0 and args.multi_q == 0
-                and not args.calibrate_copy)
+                and not args.calibrate_copy and not args.reconstruct)
     if headline and not args.no_other_workloads:
         others = {}
         for name, k, w_ in OTHER_WORKLOADS:

@@ -83,6 +83,39 @@ def test_reconstruct_bit_exact(kvr, dtype, r, w, mode, mask):
             assert (kg[b, h, n:] == 7.0).all() and (vg[b, h, n:] == 7.0).all()   # rows beyond count untouched
 
 
+@pytest.mark.parametrize("w,mask,B,Hkv", [(50, 2, 1, 3), (341, 3, 2, 8), (273, 0, 1, 1), (9, 1, 3, 5)])
+def test_reconstruct_long_lists_through_lds(kvr, w, mask, B, Hkv):
+    """bf16, three rows, a list of 4096 tokens or more: the sketch is copied into LDS chunk by chunk
+    and every (unit, tensor, half row, token slice) has a workgroup of its own.  Several token tiles
+    per workgroup, several slices per unit, unit counts that are no multiple of 8, a ragged last
+    tile, an empty unit, every sign setting, the widest sketch the route takes (3 w = 1023 rows).
+    Bit for bit against the oracle; rows beyond a unit's count stay untouched."""
+    dtype = torch.bfloat16
+    say("reconstruct through LDS", w, mask, B, Hkv)
+    rng = np.random.default_rng(300 + w)
+    cap, D = 6200, 128
+    d = kvr.make_desc(B, Hkv, Hkv, 3, w, dtype, seed=910 + w, sign_mask=mask)
+    params = kvr.desc_hash_params(d)
+    SK = U.rand_storage(rng, (B, Hkv, 3, w, D), dtype, 3.0)
+    SV = U.rand_storage(rng, (B, Hkv, 3, w, D), dtype, 3.0)
+    pos = rng.integers(0, 2000000, size=(B, Hkv, cap)).astype(np.int32)
+    pool = [6200, 4097, 0, 2049, 1, 6137, 64, 5000]
+    count = np.array([pool[i % len(pool)] for i in range(B * Hkv)], dtype=np.int32).reshape(B, Hkv)
+    k_out = torch.full((B, Hkv, cap, D), 7.0, dtype=dtype, device="cuda")
+    v_out = torch.full((B, Hkv, cap, D), 7.0, dtype=dtype, device="cuda")
+    kvr.kvr_reconstruct(d, U.to_dev(SK, dtype), U.to_dev(SV, dtype), torch.as_tensor(pos).cuda(),
+                        torch.as_tensor(count).cuda(), cap, k_out, v_out)
+    torch.cuda.synchronize()
+    kg, vg = U.to_np(k_out), U.to_np(v_out)
+    for b in range(B):
+        for h in range(Hkv):
+            n = count[b, h]
+            kr, vr = O.query(SK[b, h], SV[b, h], params, pos[b, h, :n], storage="bf16", sign_mask=mask)
+            assert np.array_equal(kg[b, h, :n], kr), (b, h)
+            assert np.array_equal(vg[b, h, :n], vr), (b, h)
+            assert (kg[b, h, n:] == 7.0).all() and (vg[b, h, n:] == 7.0).all()
+
+
 # ----------------------------------------------------------------------------- encode
 def run_encode_case(kvr, dtype, r, w, cap, counts, src_rows, mask, seed, preload=True, bad_slot=False):
     rng = np.random.default_rng(seed)
