@@ -120,9 +120,13 @@ __global__ __launch_bounds__(SORT_MAX_SEGS * WAVE) void encode_sort_kernel(
   for (int i = tid; i < segs * w; i += blockDim.x) s_tab[i] = 0;
   __syncthreads();
   int* mine = s_tab + wave * w;
-  for (int e = lo + lane; e < hi; e += WAVE) {
-    const int s = bk[e];
-    if (s >= 0) atomicAdd(&mine[s], 1);
+  for (int e0 = lo + lane; e0 < hi; e0 += 8 * WAVE) {      // eight loads in flight per lane
+    int s8[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s8[u] = (e0 + u * WAVE < hi) ? bk[e0 + u * WAVE] : -1;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s8[u] >= 0) atomicAdd(&mine[s8[u]], 1);
   }
   __syncthreads();
   for (int s = tid; s < w; s += blockDim.x) {
@@ -158,34 +162,47 @@ __global__ __launch_bounds__(SORT_MAX_SEGS * WAVE) void encode_sort_kernel(
   }
   __syncthreads();
   volatile int* cur = mine;
-  for (int e0 = lo; e0 < hi; e0 += WAVE) {
-    const int e = e0 + lane;
-    const int s = (e < hi) ? bk[e] : -1;
-    // what the accumulation needs of this token, so that it does not have to chase
-    // the ordinal: its source row and, in the top bit, whether g_row(J) = -1
-    int rec = 0;
-    if (s >= 0) {
-      rec = src_slot[(size_t)unit * cap + e];
-      if (sign_neg(d, row, tok_pos[(size_t)unit * cap + e])) rec |= (int)0x80000000u;
-    }
-    // lanes with the same slot: one ballot per bit of the slot number (13 bits cover
-    // the largest w of this path; -1 = no token gets a bit pattern of its own)
-    unsigned long long same = ~0ull;
-    const unsigned su = (unsigned)s & 0x3fffu;
+  constexpr int NA = 4;                       // 64-token chunks whose loads are requested together
+  for (int e00 = lo; e00 < hi; e00 += NA * WAVE) {
+    int s4[NA], slot4[NA], pos4[NA];
 #pragma unroll
-    for (int bit = 0; bit < 14; ++bit) {
-      const bool one = (su >> bit) & 1u;
-      const unsigned long long bal = __ballot(one);
-      same &= one ? bal : ~bal;
+    for (int u = 0; u < NA; ++u) {
+      const int e = e00 + u * WAVE + lane;
+      const bool in = e < hi;
+      s4[u] = in ? bk[e] : -1;
+      slot4[u] = in ? src_slot[(size_t)unit * cap + e] : 0;
+      pos4[u] = in ? tok_pos[(size_t)unit * cap + e] : 0;
     }
-    const int lower = __popcll(same & ((1ull << lane) - 1ull));
-    const bool higher = (lane < WAVE - 1) && ((same >> (lane + 1)) != 0ull);
-    if (s >= 0) {
-      const int dst = cur[s] + lower;
-      order[dst] = rec;
-      if (!higher) cur[s] = dst + 1;       // read above, written here by one lane per slot: same wave, program order
+#pragma unroll
+    for (int u = 0; u < NA; ++u) {
+      if (e00 + u * WAVE >= hi) break;        // uniform over the wave
+      const int s = s4[u];
+      // what the accumulation needs of this token, so that it does not have to chase
+      // the ordinal: its source row and, in the top bit, whether g_row(J) = -1
+      int rec = 0;
+      if (s >= 0) {
+        rec = slot4[u];
+        if (sign_neg(d, row, pos4[u])) rec |= (int)0x80000000u;
+      }
+      // lanes with the same slot: one ballot per bit of the slot number (13 bits cover
+      // the largest w of this path; -1 = no token gets a bit pattern of its own)
+      unsigned long long same = ~0ull;
+      const unsigned su = (unsigned)s & 0x3fffu;
+#pragma unroll
+      for (int bit = 0; bit < 14; ++bit) {
+        const bool one = (su >> bit) & 1u;
+        const unsigned long long bal = __ballot(one);
+        same &= one ? bal : ~bal;
+      }
+      const int lower = __popcll(same & ((1ull << lane) - 1ull));
+      const bool higher = (lane < WAVE - 1) && ((same >> (lane + 1)) != 0ull);
+      if (s >= 0) {
+        const int dst = cur[s] + lower;
+        order[dst] = rec;
+        if (!higher) cur[s] = dst + 1;     // read above, written here by one lane per slot: same wave, program order
+      }
+      __builtin_amdgcn_wave_barrier();
     }
-    __builtin_amdgcn_wave_barrier();
   }
 }
 
